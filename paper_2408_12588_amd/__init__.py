@@ -1,0 +1,20 @@
+"""MI355X-native hot path of Pyramid Attention Broadcast: broadcast schedule,
+device-side broadcast cache and the spatial / temporal / cross attention
+kernels behind the C-ABI library ``libpab.so``.
+
+``paper_2408_12588_amd.workloads`` (shapes and seeded inputs) can be imported
+without the library; everything else comes from ``paper_2408_12588_amd.pab``,
+which loads ``libpab.so`` and raises if it has not been built.
+"""
+import importlib
+
+_PAB_NAMES = None
+
+
+def __getattr__(name):
+    if name in ("pab", "workloads"):
+        return importlib.import_module("." + name, __name__)
+    pab = importlib.import_module(".pab", __name__)
+    if hasattr(pab, name):
+        return getattr(pab, name)
+    raise AttributeError(name)

@@ -1,0 +1,42 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def golden_path(name):
+    return os.path.join(ROOT, "tests", "golden", name)
+
+
+@pytest.fixture(scope="session")
+def golden_schedule_rows():
+    rows = []
+    with open(golden_path("schedule_tables.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, n_steps, lo, hi, n, pattern = line.split()
+            rows.append((name, int(n_steps), int(lo), int(hi), int(n), pattern))
+    return rows
+
+
+@pytest.fixture(scope="session")
+def golden_attention():
+    out = {}
+    with open(golden_path("attention_worked.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = line.split()
+            out[parts[0]] = [float(x) for x in parts[1:]]
+    return out
