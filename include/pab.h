@@ -1,0 +1,162 @@
+/*
+ * pab.h -- C ABI of libpab: the attention hot path of Pyramid Attention
+ * Broadcast (PAB) for one MI355X (gfx950).
+ *
+ * PAB (paper Sec. 2.3) speeds up a video diffusion transformer by computing
+ * each attention kind only at some diffusion steps and handing the output of
+ * the last computed step to the following steps unchanged.  This library holds
+ * exactly that path: the compute-or-reuse schedule (Eq. 1), a device-resident
+ * cache of the broadcast outputs keyed by (block, kind), and the three
+ * attention kernels (Sec. 2.1: spatial, temporal, cross).
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers owned by the caller, 16-byte
+ *     aligned, dense, in the layouts given below.  The library never allocates,
+ *     frees or copies device memory and never synchronises a stream.
+ *   - Activations are laid out [T, S, H, D]: T latent frames, S tokens per
+ *     frame, H heads, D head dim, D contiguous.  Spatial and temporal attention
+ *     read the same buffers (batch = T / sequence = S, resp. batch = S /
+ *     sequence = T); no transposed copy is ever made.  Cross-attention keys and
+ *     values are [L, H, D] for L text tokens.
+ *   - Element type is bf16 (PAB_BF16) or fp32 (PAB_F32) for q, k, v and the
+ *     output alike.  Arithmetic: operands rounded to bf16, products and softmax
+ *     accumulated in fp32, output rounded once to the element type.
+ *   - Supported head dims: 32 and 72.
+ *   - Every function returns PAB_OK (0) or a negative pab_status; nothing
+ *     aborts or throws across this boundary.  pab_last_error() gives the text
+ *     of the calling thread's last failure.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  Kernels are launched on it asynchronously.
+ */
+#ifndef PAB_H
+#define PAB_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* attention kinds (paper Sec. 2.1) */
+enum pab_kind { PAB_SPATIAL = 0, PAB_TEMPORAL = 1, PAB_CROSS = 2 };
+/* schedule decisions (paper Eq. 1: F(X_t) computed, Y*_t reused) */
+enum pab_decision { PAB_COMPUTE = 0, PAB_REUSE = 1 };
+enum pab_status {
+  PAB_OK = 0,
+  PAB_EINVAL = -1,  /* bad argument: kind, step, block, shape, dtype, alignment, NULL */
+  PAB_ESTATE = -2,  /* reuse asked of a slot never written; step went backwards      */
+  PAB_ENOMEM = -3,  /* workspace smaller than pab_workspace_bytes()                  */
+  PAB_EDEVICE = -4  /* a HIP call failed                                             */
+};
+enum pab_dtype { PAB_BF16 = 0, PAB_F32 = 1 };
+
+/*
+ * One video-generation run.  interval[kind] is the paper's "broadcast range" n
+ * of that kind (App. A.2.1: e.g. 2 / 4 / 6 for spatial / temporal / cross):
+ * one computed step, then n-1 reused steps.  1 = never reuse (the no-PAB
+ * baseline), 0 = the model has no attention of that kind (no cache slot).
+ * [range_lo, range_hi] is the inclusive, 0-based window of diffusion steps
+ * (denoising order, 0 = first / noisiest) in which broadcasting is active
+ * (the paper's "diffusion timesteps" column, the stable middle segment of
+ * Sec. 2.2); outside it every step is computed.
+ */
+typedef struct pab_config {
+  int n_blocks;   /* transformer blocks; cache slots are keyed (block, kind) */
+  int T, S;       /* latent frames, tokens per frame                          */
+  int L;          /* text tokens for cross attention (ignored if interval[2]==0) */
+  int heads, head_dim;
+  int dtype;      /* enum pab_dtype */
+  int n_steps;    /* diffusion steps of the run */
+  int interval[3];
+  int range_lo, range_hi;
+} pab_config;
+
+typedef struct pab_ctx pab_ctx;
+
+/*
+ * Eq. 1 as a pure function (host, no device access, no state).
+ * Inside [range_lo, range_hi] step s is computed iff (s - range_lo) is a
+ * multiple of interval (the period is anchored at the first step of the
+ * window); outside the window it is always computed.
+ * Returns PAB_COMPUTE or PAB_REUSE; PAB_EINVAL if kind is not a pab_kind,
+ * step < 0, interval < 1 or range_lo > range_hi.  `kind` does not change the
+ * decision (the per-kind range is the caller's `interval`); it is validated.
+ */
+int pab_schedule(int kind, int step, int range_lo, int range_hi, int interval);
+
+/*
+ * Step whose computed output is delivered at `step` under the same schedule:
+ * `step` itself if it computes, else the computed step that opened the current
+ * broadcast run.  Negative pab_status on the errors of pab_schedule.
+ */
+int pab_source_step(int kind, int step, int range_lo, int range_hi, int interval);
+
+/*
+ * Bytes of device memory the broadcast cache of `cfg` needs: one output tensor
+ * [T, S, H, D] per (block, present kind), each slot rounded up to 256 bytes.
+ * Returns 0 if cfg is NULL or invalid (pab_last_error says why).
+ */
+size_t pab_workspace_bytes(const pab_config *cfg);
+
+/*
+ * Create a context over a caller-owned device workspace (paper Sec. 2.3: the
+ * retained outputs Y*).  `workspace` must be 256-byte aligned, at least
+ * pab_workspace_bytes(cfg) long, and must outlive the context.  The library
+ * owns only the small host-side pab_ctx.  All slots start invalid.
+ * Errors: PAB_EINVAL (NULL, bad shape / dtype / head_dim / interval / window,
+ * misaligned workspace), PAB_ENOMEM (workspace too small).
+ */
+int pab_create(const pab_config *cfg, void *workspace, size_t workspace_bytes, pab_ctx **out);
+
+/* Start a new video: every slot invalid again, step history cleared. */
+int pab_reset(pab_ctx *ctx);
+
+/*
+ * One attention call of the denoising loop (paper Sec. 2.3, Eq. 1).
+ * Looks up the schedule for (kind, step).  On PAB_COMPUTE it launches the
+ * kernel of that kind on `hip_stream`, writing straight into cache slot
+ * (block, kind); on PAB_REUSE it launches nothing and reads nothing (q, k, v
+ * may be NULL or hold anything).  Either way *out receives the device pointer
+ * of the slot, which holds -- once the stream reaches this point -- the
+ * output [T, S, H, D] of the last computed step.  *out is borrowed and
+ * read-only: valid until the next computed step of the same (block, kind),
+ * pab_reset or pab_destroy.
+ *   q: [T, S, H, D];  k, v: [T, S, H, D] (spatial, temporal) or [L, H, D] (cross).
+ * Returns the decision taken (PAB_COMPUTE / PAB_REUSE) or a negative status:
+ * PAB_EINVAL (NULL ctx/out, block or kind or step out of range, kind absent
+ * from the config, NULL or misaligned q/k/v on a computed step), PAB_ESTATE
+ * (reuse of a slot never written, or step smaller than the last step seen for
+ * this (block, kind) since the last reset), PAB_EDEVICE (launch failed).
+ * Never synchronises.
+ */
+int pab_attention(pab_ctx *ctx, int block, int kind, int step, const void *q, const void *k,
+                  const void *v, void *hip_stream, const void **out);
+
+/*
+ * The attention operation alone (paper Sec. 2.1), no schedule and no cache:
+ * o = softmax(q k^T / sqrt(D)) v of the given kind, written to `o`
+ * ([T, S, H, D], same dtype), one kernel launch on `hip_stream`.  This is the
+ * launch pab_attention performs on a computed step.
+ * Errors: PAB_EINVAL (NULL / misaligned pointers, T, S, heads < 1, L < 1 for
+ * cross, unsupported head_dim or dtype), PAB_EDEVICE.
+ */
+int pab_attention_compute(int kind, int dtype, int T, int S, int L, int heads, int head_dim,
+                          const void *q, const void *k, const void *v, void *o, void *hip_stream);
+
+/* Kernel launches issued through ctx since pab_create / the last pab_reset
+ * (equals the schedule's number of computed calls); -1 if ctx is NULL. */
+long long pab_launch_count(const pab_ctx *ctx);
+
+/* Device pointer of slot (block, kind) without touching any state, or NULL. */
+const void *pab_slot_ptr(const pab_ctx *ctx, int block, int kind);
+
+/* Free the host-side context (the workspace stays the caller's). */
+int pab_destroy(pab_ctx *ctx);
+
+/* Text of the calling thread's last error ("" if none).  Never NULL. */
+const char *pab_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAB_H */

@@ -1,0 +1,84 @@
+// Shared device helpers for the gfx950 attention kernels: vector types, the
+// bf16 MFMA wrapper with its operand / accumulator lane layouts, loads that
+// round to bf16 on the way in, and stores that round once on the way out.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace pab {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// v_mfma_f32_32x32x16_bf16: D[32x32] += A[32x16] * B[16x32], one wavefront.
+//   lane l, j = l % 32, g = l / 32
+//   A operand: row j of A, columns 8g .. 8g+7       (8 bf16 per lane)
+//   B operand: column j of B, rows 8g .. 8g+7       (8 bf16 per lane)
+//   D / C:     column j, rows 8*(r/4) + 4g + r%4    (r = 0..15, fp32)
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row permutation used for the "keys" operand of the first product: lane row i
+// of A is fed key sigma(i) (bits 2 and 3 of i swapped).  With it, accumulator
+// register r of lane (j, g) holds key 16*(r/8) + 8g + r%8, i.e. registers
+// 8m .. 8m+7 are exactly the B operand (8 consecutive keys 16m + 8g ..) of the
+// second product, so probabilities never leave registers.
+__device__ __forceinline__ int sigma(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
+__device__ __forceinline__ int key_of_reg(int r, int g) { return 16 * (r >> 3) + 8 * g + (r & 7); }
+
+template <typename T> struct Io;  // element type of q, k, v, o in memory
+
+template <> struct Io<bf16_t> {
+  static __device__ __forceinline__ bf16x8 load8(const bf16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
+  static __device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d) {
+    bf16x4 v;
+    v[0] = (bf16_t)a; v[1] = (bf16_t)b; v[2] = (bf16_t)c; v[3] = (bf16_t)d;
+    *reinterpret_cast<bf16x4 *>(p) = v;
+  }
+};
+
+template <> struct Io<float> {
+  static __device__ __forceinline__ bf16x8 load8(const float *p) {
+    const f32x4 a = *reinterpret_cast<const f32x4 *>(p);
+    const f32x4 b = *reinterpret_cast<const f32x4 *>(p + 4);
+    bf16x8 v;
+    v[0] = (bf16_t)a[0]; v[1] = (bf16_t)a[1]; v[2] = (bf16_t)a[2]; v[3] = (bf16_t)a[3];
+    v[4] = (bf16_t)b[0]; v[5] = (bf16_t)b[1]; v[6] = (bf16_t)b[2]; v[7] = (bf16_t)b[3];
+    return v;
+  }
+  static __device__ __forceinline__ void store4(float *p, float a, float b, float c, float d) {
+    f32x4 v = {a, b, c, d};
+    *reinterpret_cast<f32x4 *>(p) = v;
+  }
+};
+
+__device__ __forceinline__ bf16x8 zero8() {
+  bf16x8 z;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) z[e] = (bf16_t)0.0f;
+  return z;
+}
+
+__device__ __forceinline__ bf16x8 splat8(float x) {
+  bf16x8 z;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) z[e] = (bf16_t)x;
+  return z;
+}
+
+// Head-dim dependent tile constants.
+template <int D> struct HeadDim {
+  static_assert(D % 8 == 0, "head dim must be a multiple of 8");
+  static constexpr int DK = (D + 15) / 16 * 16;       // contraction length of q.k, zero padded
+  static constexpr int KSTEPS = DK / 16;              // MFMA steps of the first product
+  static constexpr int DV = (D + 1 + 31) / 32 * 32;   // output rows incl. the all-ones row at index D
+  static constexpr int DT = DV / 32;                  // 32-row output tiles
+  static constexpr int CH = D / 8;                    // 8-element chunks per head row
+  static constexpr int DKP = DK + 8;                  // LDS row pitch (elements) of row-major tiles
+};
+
+}  // namespace pab

@@ -1,0 +1,272 @@
+// libpab: C-ABI entry points (declared in include/pab.h), the host-side
+// broadcast schedule and cache bookkeeping, and the kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/pab.h"
+#include "attn_temporal.hpp"
+#include "attn_tile.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool kind_ok(int kind) { return kind == PAB_SPATIAL || kind == PAB_TEMPORAL || kind == PAB_CROSS; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t elem_size(int dtype) { return dtype == PAB_BF16 ? 2 : 4; }
+
+// ---- launches -----------------------------------------------------------------
+
+constexpr int TILE_NQT = 2;   // 32-query tiles per wavefront
+constexpr int TILE_KB = 64;   // keys per LDS block
+
+template <typename T, int D>
+int launch_tile(int n_batch, int n_head, int sq, int sk, long long q_bs, long long q_ss, long long kv_bs,
+                long long kv_ss, const void *q, const void *k, const void *v, void *o, hipStream_t st) {
+  pab::TileParams p;
+  p.q = q; p.k = k; p.v = v; p.o = o;
+  p.n_batch = n_batch; p.n_head = n_head; p.sq = sq; p.sk = sk;
+  p.q_bs = q_bs; p.q_ss = q_ss; p.k_bs = kv_bs; p.k_ss = kv_ss; p.v_bs = kv_bs; p.v_ss = kv_ss;
+  p.o_bs = q_bs; p.o_ss = q_ss;
+  p.c = (float)(1.4426950408889634 / std::sqrt((double)D));
+  constexpr int QBLK = 128 * TILE_NQT;
+  p.n_qblk = (sq + QBLK - 1) / QBLK;
+  const long long n_bh = (long long)n_batch * n_head;
+  const long long grid = (n_bh + 7) / 8 * 8 * p.n_qblk;
+  if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "problem too large for one launch (%lld workgroups)", grid);
+  hipLaunchKernelGGL((pab::attn_tile_kernel<T, D, TILE_NQT, TILE_KB>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  return PAB_OK;
+}
+
+template <typename T, int D>
+int launch_temporal(int T_, int S, int H, const void *q, const void *k, const void *v, void *o, hipStream_t st) {
+  const long long row = (long long)H * D;
+  if (T_ > 32) {
+    // long clips: frames become the sequence of the tiled kernel, positions its batch
+    return launch_tile<T, D>(S, H, T_, T_, row, (long long)S * row, row, (long long)S * row, q, k, v, o, st);
+  }
+  pab::TemporalParams p;
+  p.q = q; p.k = k; p.v = v; p.o = o;
+  p.T = T_; p.n_head = H;
+  const long long n_prob = (long long)S * H;
+  if (n_prob > 0x7fffffffLL) return fail(PAB_EINVAL, "too many temporal problems");
+  p.n_prob = (int)n_prob;
+  p.ss = (long long)S * row;
+  p.c = (float)(1.4426950408889634 / std::sqrt((double)D));
+  long long grid = (n_prob + 3) / 4;
+  if (grid > 8192) grid = 8192;   // wavefronts loop over problems beyond this
+  if (T_ <= 16)
+    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 16>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  else
+    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 32>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  return PAB_OK;
+}
+
+template <typename T, int D>
+int launch_kind(int kind, int T_, int S, int L, int H, const void *q, const void *k, const void *v, void *o,
+                hipStream_t st) {
+  const long long row = (long long)H * D;
+  switch (kind) {
+    case PAB_SPATIAL:   // batch = frames, sequence = tokens of the frame
+      return launch_tile<T, D>(T_, H, S, S, (long long)S * row, row, (long long)S * row, row, q, k, v, o, st);
+    case PAB_TEMPORAL:  // batch = positions, sequence = frames
+      return launch_temporal<T, D>(T_, S, H, q, k, v, o, st);
+    default: {          // cross: every video token against the L text tokens
+      const long long tok = (long long)T_ * S;
+      if (tok > 0x7fffffffLL) return fail(PAB_EINVAL, "too many tokens");
+      return launch_tile<T, D>(1, H, (int)tok, L, 0, row, 0, row, q, k, v, o, st);
+    }
+  }
+}
+
+int check_shape(int kind, int dtype, int T_, int S, int L, int H, int D) {
+  if (!kind_ok(kind)) return fail(PAB_EINVAL, "kind %d is not spatial(0)/temporal(1)/cross(2)", kind);
+  if (dtype != PAB_BF16 && dtype != PAB_F32) return fail(PAB_EINVAL, "dtype %d is not bf16(0)/f32(1)", dtype);
+  if (D != 32 && D != 72) return fail(PAB_EINVAL, "head_dim %d unsupported (32 or 72)", D);
+  if (T_ < 1 || S < 1 || H < 1) return fail(PAB_EINVAL, "T=%d S=%d heads=%d must all be >= 1", T_, S, H);
+  if (kind == PAB_CROSS && L < 1) return fail(PAB_EINVAL, "cross attention needs L >= 1 text tokens (L=%d)", L);
+  if ((long long)T_ * S * H * D > (1LL << 40)) return fail(PAB_EINVAL, "tensor too large");
+  return PAB_OK;
+}
+
+int launch_checked(int kind, int dtype, int T_, int S, int L, int H, int D, const void *q, const void *k,
+                   const void *v, void *o, hipStream_t st) {
+  int rc;
+  if (dtype == PAB_BF16)
+    rc = (D == 72) ? launch_kind<pab::bf16_t, 72>(kind, T_, S, L, H, q, k, v, o, st)
+                   : launch_kind<pab::bf16_t, 32>(kind, T_, S, L, H, q, k, v, o, st);
+  else
+    rc = (D == 72) ? launch_kind<float, 72>(kind, T_, S, L, H, q, k, v, o, st)
+                   : launch_kind<float, 32>(kind, T_, S, L, H, q, k, v, o, st);
+  if (rc != PAB_OK) return rc;
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+  return PAB_OK;
+}
+
+size_t slot_bytes_of(const pab_config &c) {
+  const size_t raw = (size_t)c.T * c.S * c.heads * c.head_dim * elem_size(c.dtype);
+  return (raw + 255) / 256 * 256;
+}
+
+int check_config(const pab_config *c) {
+  if (!c) return fail(PAB_EINVAL, "config is NULL");
+  if (c->n_blocks < 1) return fail(PAB_EINVAL, "n_blocks=%d must be >= 1", c->n_blocks);
+  if (c->n_steps < 1) return fail(PAB_EINVAL, "n_steps=%d must be >= 1", c->n_steps);
+  int present = 0;
+  for (int k = 0; k < 3; ++k) {
+    if (c->interval[k] < 0) return fail(PAB_EINVAL, "interval[%d]=%d must be >= 0", k, c->interval[k]);
+    present += c->interval[k] > 0;
+  }
+  if (!present) return fail(PAB_EINVAL, "no attention kind present (all intervals 0)");
+  if (c->range_lo < 0 || c->range_lo > c->range_hi)
+    return fail(PAB_EINVAL, "window [%d, %d] must satisfy 0 <= lo <= hi", c->range_lo, c->range_hi);
+  const int kind_for_shape = c->interval[PAB_CROSS] > 0 ? PAB_CROSS : PAB_SPATIAL;
+  return check_shape(kind_for_shape, c->dtype, c->T, c->S, c->L, c->heads, c->head_dim);
+}
+
+}  // namespace
+
+struct pab_ctx {
+  pab_config cfg;
+  unsigned char *workspace;
+  size_t slot_bytes;
+  int slot_of_kind[3];   // index of the kind among the present kinds, -1 if absent
+  int n_present;
+  std::vector<int> last_step;      // per (block, kind): last step seen since reset, -1 if none
+  std::vector<int> computed_step;  // per (block, kind): step whose output the slot holds, -1 if none
+  long long launches;
+};
+
+extern "C" {
+
+int pab_schedule(int kind, int step, int range_lo, int range_hi, int interval) {
+  if (!kind_ok(kind)) return fail(PAB_EINVAL, "kind %d is not spatial(0)/temporal(1)/cross(2)", kind);
+  if (step < 0) return fail(PAB_EINVAL, "step %d is negative", step);
+  if (interval < 1) return fail(PAB_EINVAL, "interval %d must be >= 1", interval);
+  if (range_lo > range_hi) return fail(PAB_EINVAL, "window [%d, %d] is empty", range_lo, range_hi);
+  if (step < range_lo || step > range_hi) return PAB_COMPUTE;
+  return ((step - range_lo) % interval == 0) ? PAB_COMPUTE : PAB_REUSE;
+}
+
+int pab_source_step(int kind, int step, int range_lo, int range_hi, int interval) {
+  const int d = pab_schedule(kind, step, range_lo, range_hi, interval);
+  if (d < 0) return d;
+  if (d == PAB_COMPUTE) return step;
+  return step - (step - range_lo) % interval;
+}
+
+size_t pab_workspace_bytes(const pab_config *cfg) {
+  if (check_config(cfg) != PAB_OK) return 0;
+  int present = 0;
+  for (int k = 0; k < 3; ++k) present += cfg->interval[k] > 0;
+  return slot_bytes_of(*cfg) * (size_t)present * (size_t)cfg->n_blocks;
+}
+
+int pab_create(const pab_config *cfg, void *workspace, size_t workspace_bytes, pab_ctx **out) {
+  if (!out) return fail(PAB_EINVAL, "out is NULL");
+  *out = nullptr;
+  const int rc = check_config(cfg);
+  if (rc != PAB_OK) return rc;
+  if (!workspace) return fail(PAB_EINVAL, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(PAB_EINVAL, "workspace must be 256-byte aligned");
+  const size_t need = pab_workspace_bytes(cfg);
+  if (workspace_bytes < need)
+    return fail(PAB_ENOMEM, "workspace has %zu bytes, the cache needs %zu", workspace_bytes, need);
+  pab_ctx *ctx = new (std::nothrow) pab_ctx;
+  if (!ctx) return fail(PAB_ENOMEM, "out of host memory");
+  ctx->cfg = *cfg;
+  ctx->workspace = static_cast<unsigned char *>(workspace);
+  ctx->slot_bytes = slot_bytes_of(*cfg);
+  ctx->n_present = 0;
+  for (int k = 0; k < 3; ++k) ctx->slot_of_kind[k] = cfg->interval[k] > 0 ? ctx->n_present++ : -1;
+  ctx->last_step.assign((size_t)cfg->n_blocks * 3, -1);
+  ctx->computed_step.assign((size_t)cfg->n_blocks * 3, -1);
+  ctx->launches = 0;
+  *out = ctx;
+  return PAB_OK;
+}
+
+int pab_reset(pab_ctx *ctx) {
+  if (!ctx) return fail(PAB_EINVAL, "ctx is NULL");
+  std::fill(ctx->last_step.begin(), ctx->last_step.end(), -1);
+  std::fill(ctx->computed_step.begin(), ctx->computed_step.end(), -1);
+  ctx->launches = 0;
+  return PAB_OK;
+}
+
+const void *pab_slot_ptr(const pab_ctx *ctx, int block, int kind) {
+  if (!ctx || !kind_ok(kind) || block < 0 || block >= ctx->cfg.n_blocks || ctx->slot_of_kind[kind] < 0) return nullptr;
+  return ctx->workspace + ((size_t)block * ctx->n_present + ctx->slot_of_kind[kind]) * ctx->slot_bytes;
+}
+
+int pab_attention(pab_ctx *ctx, int block, int kind, int step, const void *q, const void *k, const void *v,
+                  void *hip_stream, const void **out) {
+  if (!ctx) return fail(PAB_EINVAL, "ctx is NULL");
+  if (!out) return fail(PAB_EINVAL, "out is NULL");
+  *out = nullptr;
+  const pab_config &c = ctx->cfg;
+  if (!kind_ok(kind)) return fail(PAB_EINVAL, "kind %d is not spatial(0)/temporal(1)/cross(2)", kind);
+  if (c.interval[kind] == 0) return fail(PAB_EINVAL, "kind %d is absent from this config (interval 0)", kind);
+  if (block < 0 || block >= c.n_blocks) return fail(PAB_EINVAL, "block %d outside [0, %d)", block, c.n_blocks);
+  if (step < 0 || step >= c.n_steps) return fail(PAB_EINVAL, "step %d outside [0, %d)", step, c.n_steps);
+  const size_t cell = (size_t)block * 3 + kind;
+  if (step < ctx->last_step[cell])
+    return fail(PAB_ESTATE, "step %d after step %d for block %d kind %d without pab_reset", step,
+                ctx->last_step[cell], block, kind);
+  const int decision = pab_schedule(kind, step, c.range_lo, c.range_hi, c.interval[kind]);
+  if (decision < 0) return decision;
+  void *slot = const_cast<void *>(pab_slot_ptr(ctx, block, kind));
+  if (decision == PAB_REUSE) {
+    if (ctx->computed_step[cell] < 0)
+      return fail(PAB_ESTATE, "reuse at step %d but block %d kind %d was never computed", step, block, kind);
+  } else {
+    if (!q || !k || !v) return fail(PAB_EINVAL, "q, k, v must be non-NULL on a computed step");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return fail(PAB_EINVAL, "q, k, v must be 16-byte aligned");
+    const int rc = launch_checked(kind, c.dtype, c.T, c.S, c.L, c.heads, c.head_dim, q, k, v, slot,
+                                  static_cast<hipStream_t>(hip_stream));
+    if (rc != PAB_OK) return rc;
+    ctx->computed_step[cell] = step;
+    ctx->launches++;
+  }
+  ctx->last_step[cell] = step;
+  *out = slot;
+  return decision;
+}
+
+int pab_attention_compute(int kind, int dtype, int T, int S, int L, int heads, int head_dim, const void *q,
+                          const void *k, const void *v, void *o, void *hip_stream) {
+  const int rc = check_shape(kind, dtype, T, S, L, heads, head_dim);
+  if (rc != PAB_OK) return rc;
+  if (!q || !k || !v || !o) return fail(PAB_EINVAL, "q, k, v, o must be non-NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
+    return fail(PAB_EINVAL, "q, k, v, o must be 16-byte aligned");
+  return launch_checked(kind, dtype, T, S, L, heads, head_dim, q, k, v, o, static_cast<hipStream_t>(hip_stream));
+}
+
+long long pab_launch_count(const pab_ctx *ctx) { return ctx ? ctx->launches : -1; }
+
+int pab_destroy(pab_ctx *ctx) {
+  if (!ctx) return fail(PAB_EINVAL, "ctx is NULL");
+  delete ctx;
+  return PAB_OK;
+}
+
+const char *pab_last_error(void) { return g_err; }
+
+}  // extern "C"

@@ -1,0 +1,211 @@
+"""Thin ctypes binding of libpab.so: argument marshalling only.
+
+Every function here has the name and meaning of the C entry point it calls
+(``include/pab.h``); tensors are torch CUDA tensors used purely as device
+memory, the stream is torch's current stream unless one is passed.  There is no
+fallback of any kind: if the library has not been built this module raises on
+import, and every step of the path runs in the library's HIP kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpab.so")
+
+SPATIAL, TEMPORAL, CROSS = 0, 1, 2
+COMPUTE, REUSE = 0, 1
+OK, EINVAL, ESTATE, ENOMEM, EDEVICE = 0, -1, -2, -3, -4
+BF16, F32 = 0, 1
+
+EXPORTS = (
+    "pab_schedule", "pab_source_step", "pab_workspace_bytes", "pab_create", "pab_reset", "pab_attention",
+    "pab_attention_compute", "pab_launch_count", "pab_slot_ptr", "pab_destroy", "pab_last_error",
+)
+
+
+class PabError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("libpab status %d: %s" % (status, message))
+        self.status = status
+
+
+class pab_config(ctypes.Structure):
+    _fields_ = [("n_blocks", ctypes.c_int), ("T", ctypes.c_int), ("S", ctypes.c_int), ("L", ctypes.c_int),
+                ("heads", ctypes.c_int), ("head_dim", ctypes.c_int), ("dtype", ctypes.c_int),
+                ("n_steps", ctypes.c_int), ("interval", ctypes.c_int * 3),
+                ("range_lo", ctypes.c_int), ("range_hi", ctypes.c_int)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libpab.so is not built (%s missing): run `python -m paper_2408_12588_amd.build` "
+            "or __graft_entry__.build(); there is no fallback path" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.pab_schedule.restype = ci
+    lib.pab_schedule.argtypes = [ci] * 5
+    lib.pab_source_step.restype = ci
+    lib.pab_source_step.argtypes = [ci] * 5
+    lib.pab_workspace_bytes.restype = ctypes.c_size_t
+    lib.pab_workspace_bytes.argtypes = [ctypes.POINTER(pab_config)]
+    lib.pab_create.restype = ci
+    lib.pab_create.argtypes = [ctypes.POINTER(pab_config), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+    lib.pab_reset.restype = ci
+    lib.pab_reset.argtypes = [vp]
+    lib.pab_attention.restype = ci
+    lib.pab_attention.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, ctypes.POINTER(vp)]
+    lib.pab_attention_compute.restype = ci
+    lib.pab_attention_compute.argtypes = [ci] * 7 + [vp] * 5
+    lib.pab_launch_count.restype = ctypes.c_longlong
+    lib.pab_launch_count.argtypes = [vp]
+    lib.pab_slot_ptr.restype = vp
+    lib.pab_slot_ptr.argtypes = [vp, ci, ci]
+    lib.pab_destroy.restype = ci
+    lib.pab_destroy.argtypes = [vp]
+    lib.pab_last_error.restype = ctypes.c_char_p
+    lib.pab_last_error.argtypes = []
+    return lib
+
+
+lib = _load()
+
+
+def pab_last_error() -> str:
+    return lib.pab_last_error().decode()
+
+
+def _check(status: int) -> int:
+    if status < 0:
+        raise PabError(status, pab_last_error())
+    return status
+
+
+def pab_schedule(kind: int, step: int, range_lo: int, range_hi: int, interval: int) -> int:
+    return _check(lib.pab_schedule(kind, step, range_lo, range_hi, interval))
+
+
+def pab_source_step(kind: int, step: int, range_lo: int, range_hi: int, interval: int) -> int:
+    return _check(lib.pab_source_step(kind, step, range_lo, range_hi, interval))
+
+
+def make_config(n_blocks, T, S, L, heads, head_dim, dtype, n_steps, interval, range_lo, range_hi) -> pab_config:
+    return pab_config(n_blocks, T, S, L, heads, head_dim, dtype, n_steps, (ctypes.c_int * 3)(*interval),
+                      range_lo, range_hi)
+
+
+def config_of(wl, intervals=None) -> pab_config:
+    """pab_config of a ``workloads.Workload`` (optionally with other broadcast ranges,
+    e.g. (1, 1, 1) masked to the present kinds for the no-broadcast baseline)."""
+    iv = tuple(wl.intervals if intervals is None else intervals)
+    iv = tuple(i if w > 0 else 0 for i, w in zip(iv, wl.intervals))
+    return make_config(wl.n_blocks, wl.T, wl.S, wl.L, wl.heads, wl.head_dim,
+                       BF16 if wl.dtype == "bf16" else F32, wl.n_steps, iv, wl.lo, wl.hi)
+
+
+def pab_workspace_bytes(cfg: pab_config) -> int:
+    n = lib.pab_workspace_bytes(ctypes.byref(cfg))
+    if n == 0:
+        raise PabError(EINVAL, pab_last_error())
+    return n
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _ptr(t) -> int:
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("libpab takes dense device tensors")
+    return t.data_ptr()
+
+
+_TORCH_DTYPE = {BF16: torch.bfloat16, F32: torch.float32}
+
+
+class PabContext:
+    """pab_create / pab_attention / pab_reset / pab_destroy over a workspace
+    tensor that this object keeps alive (the C library only borrows it)."""
+
+    def __init__(self, cfg: pab_config, device="cuda:0", workspace: torch.Tensor | None = None):
+        self.cfg = cfg
+        need = pab_workspace_bytes(cfg)
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=device)
+        self.workspace = workspace
+        handle = ctypes.c_void_p()
+        _check(lib.pab_create(ctypes.byref(cfg), workspace.data_ptr(), workspace.numel(), ctypes.byref(handle)))
+        self._h = handle
+        self.shape = (cfg.T, cfg.S, cfg.heads, cfg.head_dim)
+        self.dtype = _TORCH_DTYPE[cfg.dtype]
+        self._numel = cfg.T * cfg.S * cfg.heads * cfg.head_dim
+
+    def pab_attention(self, block: int, kind: int, step: int, q, k, v, stream=None):
+        """-> (decision, device pointer of the slot)."""
+        out = ctypes.c_void_p()
+        dec = _check(lib.pab_attention(self._h, block, kind, step, _ptr(q), _ptr(k), _ptr(v), _stream(stream),
+                                       ctypes.byref(out)))
+        return dec, out.value
+
+    def slot_tensor(self, block: int, kind: int) -> torch.Tensor:
+        """View of cache slot (block, kind) inside the workspace tensor (no copy)."""
+        p = lib.pab_slot_ptr(self._h, block, kind)
+        if not p:
+            raise PabError(EINVAL, "no such slot")
+        off = p - self.workspace.data_ptr()
+        nbytes = self._numel * self.workspace.new_empty(0, dtype=self.dtype).element_size()
+        return self.workspace[off:off + nbytes].view(self.dtype).view(self.shape)
+
+    def pab_slot_ptr(self, block: int, kind: int) -> int:
+        return lib.pab_slot_ptr(self._h, block, kind) or 0
+
+    def pab_reset(self):
+        _check(lib.pab_reset(self._h))
+
+    def pab_launch_count(self) -> int:
+        return lib.pab_launch_count(self._h)
+
+    def pab_destroy(self):
+        if self._h:
+            _check(lib.pab_destroy(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.pab_destroy()
+        except Exception:
+            pass
+
+
+def pab_attention_compute(kind: int, q, k, v, out=None, L: int | None = None, stream=None):
+    """One attention launch without schedule or cache.  q ``[T, S, H, D]``;
+    k, v ``[T, S, H, D]`` (spatial, temporal) or ``[L, H, D]`` (cross)."""
+    T, S, H, D = q.shape
+    dtype = BF16 if q.dtype == torch.bfloat16 else F32
+    if q.dtype not in (torch.bfloat16, torch.float32) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share dtype bf16 or f32")
+    if kind == CROSS:
+        if k.dim() != 3 or tuple(k.shape[1:]) != (H, D) or v.shape != k.shape:
+            raise ValueError("cross attention wants k, v of shape [L, H, D]")
+        L = k.shape[0]
+    else:
+        if k.shape != q.shape or v.shape != q.shape:
+            raise ValueError("k, v must have the shape of q")
+        L = 0
+    if out is None:
+        out = torch.empty_like(q)
+    _check(lib.pab_attention_compute(kind, dtype, T, S, L, H, D, _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                     _stream(stream)))
+    return out

@@ -1,0 +1,208 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on
+the same seeded inputs.  Bar: schedule and reused outputs bit-exact; computed
+attention within max-abs error 1e-2 * max|V| (bf16 operands, fp32 accumulation)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pab_oracle as orc
+from paper_2408_12588_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2   # max |gpu - oracle| <= TOL * max|V|
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def pab():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2408_12588_amd import pab as mod
+    return mod
+
+
+def rand_qkv(kind, T, S, L, H, D, dtype, seed, scale_rows=0.0):
+    wl = W.Workload("case", 1, T, S, L, H, D, dtype, 1, (1, 1, 1), 0, 0, peaked_frac=scale_rows, seed=seed)
+    return W.make_qkv(wl, 0, kind, 0)
+
+
+def assert_close(got: torch.Tensor, want: np.ndarray, v: torch.Tensor, what=""):
+    got = got.detach().cpu().double().numpy()
+    assert np.isfinite(got).all(), what
+    err = np.abs(got - want).max()
+    bound = TOL * float(v.abs().max())
+    assert err <= bound, "%s: max abs err %.3e > %.3e" % (what, err, bound)
+    return err
+
+
+SHAPES = [
+    # kind, T, S, L, H, D, dtype
+    (W.SPATIAL, 2, 300, 0, 2, 72, "bf16"),     # 2 query blocks (256 + 44), 5 key blocks, ragged tail
+    (W.SPATIAL, 1, 64, 0, 1, 72, "bf16"),      # exactly one key block
+    (W.SPATIAL, 1, 65, 0, 3, 72, "bf16"),      # one key past a block edge
+    (W.SPATIAL, 3, 513, 0, 3, 72, "bf16"),     # more (batch, head) pairs than one per XCD round
+    (W.SPATIAL, 1, 1, 0, 1, 72, "bf16"),       # single token
+    (W.SPATIAL, 2, 200, 0, 2, 32, "bf16"),
+    (W.SPATIAL, 2, 130, 0, 2, 72, "f32"),
+    (W.SPATIAL, 4, 64, 0, 4, 32, "f32"),       # the Tiny configuration's spatial call
+    (W.TEMPORAL, 16, 50, 0, 4, 72, "bf16"),
+    (W.TEMPORAL, 17, 37, 0, 3, 72, "bf16"),    # 17 frames: second 16-key half almost empty
+    (W.TEMPORAL, 1, 9, 0, 2, 72, "bf16"),      # one frame: identity on V
+    (W.TEMPORAL, 4, 64, 0, 4, 32, "f32"),      # Tiny
+    (W.TEMPORAL, 32, 11, 0, 2, 72, "bf16"),    # full 32x32 tile
+    (W.TEMPORAL, 33, 7, 0, 2, 72, "bf16"),     # beyond the wavefront-resident kernel: tiled fallback
+    (W.TEMPORAL, 5, 300, 0, 16, 72, "f32"),
+    (W.TEMPORAL, 16, 33, 0, 2, 32, "bf16"),
+    (W.CROSS, 2, 300, 120, 2, 72, "bf16"),
+    (W.CROSS, 3, 100, 300, 2, 72, "bf16"),
+    (W.CROSS, 1, 70, 1, 2, 72, "bf16"),        # one text key: output = its value
+    (W.CROSS, 4, 64, 16, 4, 32, "f32"),        # Tiny
+    (W.CROSS, 2, 129, 64, 1, 72, "f32"),
+]
+
+
+@pytest.mark.parametrize("kind,T,S,L,H,D,dtype", SHAPES)
+def test_attention_matches_oracle(pab, kind, T, S, L, H, D, dtype):
+    print("case", W.KIND_NAMES[kind], T, S, L, H, D, dtype, flush=True)
+    q, k, v = rand_qkv(kind, T, S, L, H, D, dtype, seed=1000 + 7 * T + S + L)
+    out = pab.pab_attention_compute(kind, q.to(DEV), k.to(DEV), v.to(DEV))
+    torch.cuda.synchronize()
+    want = orc.kind_attention(kind, q, k, v)
+    assert out.dtype == q.dtype and out.shape == q.shape
+    assert_close(out, want, v, "shape case")
+    if kind == W.TEMPORAL and T == 1:
+        assert torch.equal(out.cpu(), v)
+    if kind == W.CROSS and L == 1:
+        assert torch.equal(out.cpu(), v.expand(T * S, H, D).reshape(T, S, H, D))
+
+
+def test_peaked_queries_small(pab):
+    # the stress configuration's value recipe (5% of query rows scaled by 8) at a size the
+    # oracle can do in full: sharp and diffuse rows share tiles
+    for kind, (T, S, L) in ((W.SPATIAL, (2, 333, 0)), (W.TEMPORAL, (16, 41, 0)), (W.CROSS, (2, 200, 120))):
+        q, k, v = rand_qkv(kind, T, S, L, 4, 72, "bf16", seed=77, scale_rows=0.05)
+        out = pab.pab_attention_compute(kind, q.to(DEV), k.to(DEV), v.to(DEV))
+        torch.cuda.synchronize()
+        assert_close(out, orc.kind_attention(kind, q, k, v), v, "peaked %d" % kind)
+
+
+def test_identical_keys_give_mean_of_values(pab):
+    T, S, H, D = 1, 200, 2, 72
+    q, k, v = rand_qkv(W.SPATIAL, T, S, 0, H, D, "bf16", seed=5)
+    k = k[:, :1].expand(T, S, H, D).contiguous()
+    out = pab.pab_attention_compute(W.SPATIAL, q.to(DEV), k.to(DEV), v.to(DEV)).cpu().double()
+    mean = v.double().mean(1, keepdim=True).expand_as(out)
+    assert (out - mean).abs().max() <= TOL * float(v.abs().max())
+
+
+def test_tiny_video_every_cell(pab):
+    """Config 1 end to end: every (step, block, kind) cell against the oracle's video run;
+    reuse steps get NaN-poisoned q/k/v, must launch nothing and return the very bytes of
+    the last computed step."""
+    wl = W.TINY
+    ctx = pab.PabContext(pab.config_of(wl), DEV)
+    ctx.workspace.fill_(0xFF)            # NaN pattern: a slot read before being written would show
+    vo = orc.VideoOracle(wl.intervals, wl.lo, wl.hi)
+    poison = torch.full((wl.T, wl.S, wl.heads, wl.head_dim), float("nan"), device=DEV)
+    last_bytes = {}
+    computes = 0
+    for step in range(wl.n_steps):
+        for block, kind in wl.calls_per_step():
+            want_dec = orc.schedule(step, wl.lo, wl.hi, wl.intervals[kind])
+            if want_dec == orc.COMPUTE:
+                q, k, v = W.make_qkv(wl, block, kind, step)
+                dq, dk, dv = q.to(DEV), k.to(DEV), v.to(DEV)
+            else:
+                dq = dk = dv = poison
+            before = ctx.pab_launch_count()
+            dec, ptr = ctx.pab_attention(block, kind, step, dq, dk, dv)
+            torch.cuda.synchronize()
+            assert dec == want_dec
+            assert ptr == ctx.pab_slot_ptr(block, kind)
+            got = ctx.slot_tensor(block, kind)
+            _, want = vo.step(block, kind, step, lambda: W.make_qkv(wl, block, kind, step))
+            if dec == orc.COMPUTE:
+                computes += 1
+                assert ctx.pab_launch_count() == before + 1
+                assert_close(got, want, v, "tiny step %d block %d kind %d" % (step, block, kind))
+                last_bytes[(block, kind)] = got.clone()
+            else:
+                assert ctx.pab_launch_count() == before
+                assert torch.equal(got.view(torch.int32), last_bytes[(block, kind)].view(torch.int32))
+                assert_close(got, want, torch.ones(1), "tiny reuse")
+    assert computes == ctx.pab_launch_count() == vo.computes == 2 * (7 + 5 + 5)
+    # step going backwards without a reset is a state error; after reset it is fine
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl, 0, W.SPATIAL, 0))
+    with pytest.raises(pab.PabError) as e:
+        ctx.pab_attention(0, W.SPATIAL, 0, q, k, v)
+    assert e.value.status == pab.ESTATE
+    ctx.pab_reset()
+    assert ctx.pab_launch_count() == 0
+    with pytest.raises(pab.PabError) as e:       # reuse step first after reset: nothing cached
+        ctx.pab_attention(0, W.SPATIAL, 3, None, None, None)
+    assert e.value.status == pab.ESTATE
+    dec, _ = ctx.pab_attention(0, W.SPATIAL, 0, q, k, v)
+    assert dec == pab.COMPUTE
+    dec, _ = ctx.pab_attention(0, W.SPATIAL, 3, None, None, None)   # window step 3 reuses; NULL inputs are fine
+    assert dec == pab.REUSE
+    torch.cuda.synchronize()
+    ctx.pab_destroy()
+
+
+def test_no_broadcast_baseline_computes_every_step(pab):
+    wl = W.TINY
+    ctx = pab.PabContext(pab.config_of(wl, (1, 1, 1)), DEV)
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl, 0, W.TEMPORAL, 0))
+    for step in range(wl.n_steps):
+        dec, _ = ctx.pab_attention(1, W.TEMPORAL, step, q, k, v)
+        assert dec == pab.COMPUTE
+    torch.cuda.synchronize()
+    assert ctx.pab_launch_count() == wl.n_steps
+
+
+FULL = [(wl, kind) for wl in W.CONFIGS[1:] for kind in (W.SPATIAL, W.TEMPORAL, W.CROSS) if wl.intervals[kind] > 0]
+
+
+@pytest.mark.parametrize("wl,kind", FULL, ids=lambda x: x.name if isinstance(x, W.Workload) else W.KIND_NAMES[x])
+def test_full_size_sampled_rows(pab, wl, kind):
+    """Configs 2-5 at full size, in the launch configuration the benchmark times: one
+    computed call per kind through the cache path; a seeded sample of output rows (incl.
+    the corner rows) against the oracle, plus properties that hold at any size."""
+    print("full", wl.name, W.KIND_NAMES[kind], flush=True)
+    small = W.Workload(wl.name, 1, wl.T, wl.S, wl.L, wl.heads, wl.head_dim, wl.dtype, wl.n_steps,
+                       wl.intervals, wl.lo, wl.hi, peaked_frac=wl.peaked_frac, seed=wl.seed)
+    ctx = pab.PabContext(pab.config_of(small), DEV)
+    step = wl.lo                      # first step of the window: computed
+    q, k, v = W.make_qkv(small, 0, kind, step)
+    dq, dk, dv = q.to(DEV), k.to(DEV), v.to(DEV)
+    dec, _ = ctx.pab_attention(0, kind, step, dq, dk, dv)
+    assert dec == pab.COMPUTE
+    torch.cuda.synchronize()
+    out = ctx.slot_tensor(0, kind)
+    assert bool(torch.isfinite(out).all())
+    # every output coordinate is a convex combination of value coordinates
+    vmax, vmin = float(v.max()), float(v.min())
+    assert float(out.max()) <= vmax + 1e-2 and float(out.min()) >= vmin - 1e-2
+    rows = W.sample_rows(small, 48, seed=kind)
+    want = orc.attention_rows(kind, q, k, v, rows)
+    got = out.cpu()[rows[:, 0], rows[:, 1], rows[:, 2]].double().numpy()
+    err = np.abs(got - want).max()
+    assert err <= TOL * float(v.abs().max()), "%s %s: %.3e" % (wl.name, W.KIND_NAMES[kind], err)
+    # the next step of the window reuses: same pointer, same bytes, nothing launched
+    snap = out.clone()
+    dec, _ = ctx.pab_attention(0, kind, step + 1, None, None, None)
+    if wl.intervals[kind] > 1:
+        assert dec == pab.REUSE and ctx.pab_launch_count() == 1
+        assert torch.equal(ctx.slot_tensor(0, kind).view(torch.int16), snap.view(torch.int16))
+    ctx.pab_destroy()
+
+
+def test_full_size_temporal_complete(pab):
+    """Temporal attention of config 2 compared in full (the oracle does it in seconds)."""
+    wl = W.OPENSORA_480P
+    q, k, v = W.make_qkv(wl, 3, W.TEMPORAL, 7)
+    out = pab.pab_attention_compute(W.TEMPORAL, q.to(DEV), k.to(DEV), v.to(DEV))
+    torch.cuda.synchronize()
+    assert_close(out, orc.temporal(q, k, v), v, "config 2 temporal, all rows")

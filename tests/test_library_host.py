@@ -1,0 +1,151 @@
+"""Host-side behaviour of libpab.so that needs no GPU: the library loads, exports
+what include/pab.h declares, its schedule equals the oracle's bit for bit, and
+argument errors come back as negative status codes."""
+import ctypes
+import os
+import random
+import re
+
+import pytest
+
+from oracle import pab_oracle as orc
+from paper_2408_12588_amd import pab, workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_match_header():
+    text = open(os.path.join(ROOT, "include", "pab.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(pab_[a-z_]+)\s*\(", text))
+    assert declared == set(pab.EXPORTS)
+    for name in declared:
+        assert hasattr(pab.lib, name), name
+
+
+@pytest.mark.parametrize("wl", W.CONFIGS, ids=lambda w: w.name)
+def test_schedule_equals_oracle_on_workloads(wl):
+    for kind in range(3):
+        n = wl.intervals[kind]
+        if n == 0:
+            continue
+        for s in range(wl.n_steps):
+            assert pab.pab_schedule(kind, s, wl.lo, wl.hi, n) == orc.schedule(s, wl.lo, wl.hi, n)
+            assert pab.pab_source_step(kind, s, wl.lo, wl.hi, n) == orc.source_step(s, wl.lo, wl.hi, n)
+        # the no-broadcast baseline computes every step
+        assert all(pab.pab_schedule(kind, s, wl.lo, wl.hi, 1) == pab.COMPUTE for s in range(wl.n_steps))
+
+
+def test_schedule_golden_rows(golden_schedule_rows):
+    for name, n_steps, lo, hi, n, pattern in golden_schedule_rows:
+        got = "".join("CR"[pab.pab_schedule(0, s, lo, hi, n)] for s in range(n_steps))
+        assert got == pattern, name
+
+
+def test_schedule_fuzz_against_oracle():
+    rng = random.Random(99)
+    for _ in range(20000):
+        s = rng.randint(0, 400)
+        lo = rng.randint(0, 300)
+        hi = rng.randint(lo, 400)
+        n = rng.randint(1, 16)
+        kind = rng.randint(0, 2)
+        assert pab.pab_schedule(kind, s, lo, hi, n) == orc.schedule(s, lo, hi, n)
+        assert pab.pab_source_step(kind, s, lo, hi, n) == orc.source_step(s, lo, hi, n)
+
+
+def test_schedule_errors():
+    for args in [(3, 0, 0, 5, 2), (-1, 0, 0, 5, 2), (0, -1, 0, 5, 2), (0, 0, 0, 5, 0), (0, 0, 6, 5, 2)]:
+        assert pab.lib.pab_schedule(*args) == pab.EINVAL
+        assert pab.lib.pab_source_step(*args) == pab.EINVAL
+        assert pab.pab_last_error() != ""
+        with pytest.raises(pab.PabError):
+            pab.pab_schedule(*args)
+
+
+def test_workspace_bytes():
+    cfg = pab.config_of(W.OPENSORA_480P)
+    slot = 16 * 1590 * 16 * 72 * 2
+    assert slot % 256 == 0
+    assert pab.pab_workspace_bytes(cfg) == 28 * 3 * slot
+    assert pab.pab_workspace_bytes(pab.config_of(W.LATTE_512)) == 28 * 2 * 16 * 1024 * 16 * 72 * 2
+    tiny = pab.config_of(W.TINY)
+    assert pab.pab_workspace_bytes(tiny) == 2 * 3 * 4 * 64 * 4 * 32 * 4
+    bad = pab.config_of(W.TINY)
+    bad.head_dim = 48
+    assert pab.lib.pab_workspace_bytes(ctypes.byref(bad)) == 0 and "head_dim" in pab.pab_last_error()
+    assert pab.lib.pab_workspace_bytes(None) == 0
+
+
+def _create(cfg, ptr, nbytes):
+    h = ctypes.c_void_p()
+    rc = pab.lib.pab_create(ctypes.byref(cfg), ptr, nbytes, ctypes.byref(h))
+    return rc, h
+
+
+def test_create_and_attention_errors_without_device():
+    # pab_create only does pointer arithmetic on the workspace, so a made-up aligned
+    # address is enough to walk the error paths; nothing here launches a kernel.
+    cfg = pab.config_of(W.TINY)
+    need = pab.pab_workspace_bytes(cfg)
+    fake = 0x10000000
+    assert _create(cfg, fake, need - 1)[0] == pab.ENOMEM
+    assert _create(cfg, fake + 16, need)[0] == pab.EINVAL          # not 256-byte aligned
+    assert _create(cfg, None, need)[0] == pab.EINVAL
+    assert pab.lib.pab_create(ctypes.byref(cfg), fake, need, None) == pab.EINVAL
+    for field, val in [("n_blocks", 0), ("T", 0), ("S", -1), ("heads", 0), ("head_dim", 64), ("dtype", 7),
+                       ("n_steps", 0), ("range_lo", -1), ("range_hi", 0), ("L", 0)]:
+        bad = pab.config_of(W.TINY)
+        setattr(bad, field, val)
+        assert _create(bad, fake, need)[0] == pab.EINVAL, field
+    bad = pab.config_of(W.TINY)
+    bad.interval[1] = -1
+    assert _create(bad, fake, need)[0] == pab.EINVAL
+    bad.interval[0] = bad.interval[1] = bad.interval[2] = 0
+    assert _create(bad, fake, need)[0] == pab.EINVAL
+
+    rc, h = _create(cfg, fake, need)
+    assert rc == pab.OK and h.value
+    out = ctypes.c_void_p()
+    att = lambda *a: pab.lib.pab_attention(h, *a, ctypes.byref(out))
+    assert att(0, 3, 0, 16, 16, 16, None) == pab.EINVAL          # bad kind
+    assert att(2, 0, 0, 16, 16, 16, None) == pab.EINVAL          # block out of range
+    assert att(0, 0, 10, 16, 16, 16, None) == pab.EINVAL         # step out of range
+    assert att(0, 0, 0, None, 16, 16, None) == pab.EINVAL        # NULL q on a computed step
+    assert att(0, 0, 0, 8, 16, 16, None) == pab.EINVAL           # misaligned q
+    assert pab.lib.pab_attention(h, 0, 0, 0, 16, 16, 16, None, None) == pab.EINVAL
+    assert pab.lib.pab_attention(None, 0, 0, 0, 16, 16, 16, None, ctypes.byref(out)) == pab.EINVAL
+    # step 3 of the tiny spatial row is a reuse step, but nothing was computed yet
+    assert att(0, 0, 3, None, None, None, None) == pab.ESTATE
+    assert "never computed" in pab.pab_last_error()
+    assert pab.lib.pab_launch_count(h) == 0
+    # slots are laid out block-major, kind-minor
+    slot = 4 * 64 * 4 * 32 * 4
+    assert pab.lib.pab_slot_ptr(h, 0, 0) == fake
+    assert pab.lib.pab_slot_ptr(h, 1, 2) == fake + 5 * slot
+    assert pab.lib.pab_slot_ptr(h, 2, 0) is None and pab.lib.pab_slot_ptr(h, 0, 3) is None
+    assert pab.lib.pab_reset(h) == pab.OK
+    assert pab.lib.pab_destroy(h) == pab.OK
+    assert pab.lib.pab_destroy(None) == pab.EINVAL and pab.lib.pab_reset(None) == pab.EINVAL
+    assert pab.lib.pab_launch_count(None) == -1
+
+    # a config without cross attention has no cross slot and rejects cross calls
+    latte = pab.config_of(W.LATTE_512)
+    rc, h = _create(latte, fake, pab.pab_workspace_bytes(latte))
+    assert rc == pab.OK
+    assert pab.lib.pab_attention(h, 0, 2, 0, 16, 16, 16, None, ctypes.byref(out)) == pab.EINVAL
+    assert pab.lib.pab_slot_ptr(h, 0, 2) is None
+    assert pab.lib.pab_slot_ptr(h, 1, 1) == fake + 3 * 16 * 1024 * 16 * 72 * 2
+    pab.lib.pab_destroy(h)
+
+
+def test_compute_argument_errors_without_device():
+    f = pab.lib.pab_attention_compute
+    ok = (0, pab.BF16, 2, 8, 4, 2, 72)
+    assert f(*ok, None, 16, 16, 16, None) == pab.EINVAL
+    assert f(*ok, 16, 16, 16, 24, None) == pab.EINVAL              # misaligned o
+    assert f(0, pab.BF16, 2, 8, 4, 2, 64, 16, 16, 16, 16, None) == pab.EINVAL   # head_dim
+    assert f(2, pab.BF16, 2, 8, 0, 2, 72, 16, 16, 16, 16, None) == pab.EINVAL   # cross without keys
+    assert f(5, pab.BF16, 2, 8, 4, 2, 72, 16, 16, 16, 16, None) == pab.EINVAL
+    assert f(0, 3, 2, 8, 4, 2, 72, 16, 16, 16, 16, None) == pab.EINVAL
+    assert f(0, pab.BF16, 0, 8, 4, 2, 72, 16, 16, 16, 16, None) == pab.EINVAL
