@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the PAB attention hot path on one MI355X.
+
+A "step" is one denoising step of the named synthetic workload: every
+(block, kind) attention call of the video DiT goes through ``pab_attention``,
+which computes or reuses according to the broadcast schedule (paper Sec. 2.3,
+Eq. 1).  ``--steps`` defaults to one whole video.  Inputs are synthetic (seeded,
+bf16 N(0,1), shapes of the workload) and resident in HBM before timing starts;
+a pool of input sets larger than the last-level cache is rotated so that HBM
+numbers are not cache hits.
+
+Prints ONE JSON line: whole-job computed attention TFLOP/s under the PAB
+schedule, per-video latency with and without PAB, the roofline of the dominant
+kernel (spatial attention, bf16 MFMA) measured with stream events inside the
+timed region, per-kind rates, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="denoising steps to time (default: one video)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps first (default: one video)")
+    ap.add_argument("--workload", default="opensora_480p")
+    ap.add_argument("--pool", type=int, default=8, help="rotating input sets")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--kind-reps", type=int, default=40, help="launches per kind in the per-kind section")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2408_12588_amd import pab, workloads as W
+
+    wl = W.BY_NAME[args.workload]
+    K = args.steps if args.steps is not None else wl.n_steps
+    Wm = args.warmup if args.warmup is not None else wl.n_steps
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+
+    # ---- inputs: seeded, on device, before any timing ----
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    full = (wl.T, wl.S, wl.heads, wl.head_dim)
+    dt = wl.torch_dtype
+
+    def randn(shape):
+        return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(dt)
+
+    pool = [tuple(randn(full) for _ in range(3)) for _ in range(args.pool)]
+    if wl.peaked_frac > 0:
+        rows = torch.from_numpy(W.peaked_rows(wl)).to(dev)
+        for q, _, _ in pool:
+            q.view(wl.tokens, wl.heads, wl.head_dim)[rows] *= wl.peaked_scale
+    kv_cross = [tuple(randn((wl.L, wl.heads, wl.head_dim)) for _ in range(2)) for _ in range(args.pool)] \
+        if wl.intervals[W.CROSS] > 0 else None
+    calls = wl.calls_per_step()
+
+    def inputs(i, kind):
+        q, k, v = pool[i % args.pool]
+        if kind == W.CROSS:
+            k, v = kv_cross[i % args.pool]
+        return q, k, v
+
+    def run_steps(ctx, first_step, n, events=None):
+        """Queue n denoising steps asynchronously; returns computed FLOPs per kind."""
+        flops = [0.0, 0.0, 0.0]
+        launches = [0, 0, 0]
+        i = first_step * len(calls)
+        for s in range(first_step, first_step + n):
+            step = s % wl.n_steps
+            if step == 0:
+                ctx.pab_reset()
+            for block, kind in calls:
+                q, k, v = inputs(i, kind)
+                i += 1
+                if events is not None and kind == W.SPATIAL and \
+                        pab.pab_schedule(kind, step, wl.lo, wl.hi, ctx.cfg.interval[kind]) == pab.COMPUTE:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    dec, _ = ctx.pab_attention(block, kind, step, q, k, v)
+                    e1.record(stream)
+                    events.append((e0, e1))
+                else:
+                    dec, _ = ctx.pab_attention(block, kind, step, q, k, v)
+                if dec == pab.COMPUTE:
+                    flops[kind] += wl.flops(kind)
+                    launches[kind] += 1
+        return flops, launches
+
+    def timed(ctx, n, events=None):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        flops, launches = run_steps(ctx, 0, n, events)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, flops, launches
+
+    # ---- PAB schedule: warmup, then the timed region ----
+    ctx = pab.PabContext(pab.config_of(wl), dev)
+    run_steps(ctx, 0, Wm)
+    events = []
+    sec, flops, launches = timed(ctx, K, events)
+    spatial_ms = [a.elapsed_time(b) for a, b in events]
+    total_flops = sum(flops)
+    ctx.pab_destroy()
+
+    # ---- same library, broadcast ranges 1/1/1: the no-PAB baseline ----
+    ctx0 = pab.PabContext(pab.config_of(wl, (1, 1, 1)), dev, workspace=ctx.workspace)
+    run_steps(ctx0, 0, min(Wm, 2))
+    sec0, flops0, launches0 = timed(ctx0, K)
+    ctx0.pab_destroy()
+
+    # ---- per-kind section: back-to-back computes of one kind over the rotating pool ----
+    kinds = {}
+    out = torch.empty(full, device=dev, dtype=dt)
+    for kind in (W.SPATIAL, W.TEMPORAL, W.CROSS):
+        if wl.intervals[kind] == 0:
+            continue
+        for i in range(3):
+            pab.pab_attention_compute(kind, *inputs(i, kind), out=out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(args.kind_reps):
+            pab.pab_attention_compute(kind, *inputs(i, kind), out=out)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.kind_reps
+        tf = wl.flops(kind) / (ms * 1e-3) / 1e12
+        gbs = wl.bytes(kind) / (ms * 1e-3) / 1e9
+        kinds[W.KIND_NAMES[kind]] = {
+            "ms_per_call": round(ms, 4), "tflops": round(tf, 2), "gbs": round(gbs, 1),
+            "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}
+
+    # ---- roofline of the dominant kernel (spatial attention), from events inside the timed region ----
+    if spatial_ms:
+        avg_ms = sum(spatial_ms) / len(spatial_ms)
+        achieved = wl.flops(W.SPATIAL) / (avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "attn_tile_kernel (spatial)", "achieved": round(achieved, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": None, "avg_launch_ms": round(avg_ms, 4), "launches": len(spatial_ms),
+                    "flops_per_launch": wl.flops(W.SPATIAL)}
+    else:
+        roofline = None
+
+    # ---- schedule accounting ----
+    skipped_flop_fraction = 1.0 - total_flops / sum(flops0) if sum(flops0) else 0.0
+    time_reduction = 1.0 - sec / sec0
+
+    result = {
+        "metric": "attention TFLOP/s + %roofline; per-video attention latency PAB vs no-PAB",
+        "value": round(total_flops / sec / 1e12, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(sec * 1e3 / K, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "blocks": wl.n_blocks, "T": wl.T, "S": wl.S, "L": wl.L,
+                   "heads": wl.heads, "head_dim": wl.head_dim, "video_steps": wl.n_steps,
+                   "intervals": list(wl.intervals), "window": [wl.lo, wl.hi], "input_pool": args.pool},
+        "value_definition": "attention FLOPs actually computed under the PAB schedule / wall time of the timed steps",
+        "roofline": roofline,
+        "latency_ms": {"pab": round(sec * 1e3, 3), "no_pab": round(sec0 * 1e3, 3), "steps": K},
+        "pab": {"time_reduction": round(time_reduction, 4), "skipped_flop_fraction": round(skipped_flop_fraction, 4),
+                "launches_pab": launches, "launches_no_pab": launches0,
+                "effective_tflops": round(sum(flops0) / sec / 1e12, 3)},
+        "kinds": kinds,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(wl, target_seconds):
+    """The fp64 oracle as it stands, timed on the host cores over a bounded sample of the same
+    workload: whole frames of spatial attention (the dominant cost), sized from a one-frame probe."""
+    import numpy as np
+    from oracle import pab_oracle as orc
+    from paper_2408_12588_amd import workloads as W
+    g = np.random.default_rng(wl.seed)
+    H, D, S = wl.heads, wl.head_dim, wl.S
+
+    def frames(n):
+        return tuple(g.standard_normal((n, S, H, D)) for _ in range(3))
+
+    q, k, v = frames(1)
+    t0 = time.perf_counter()
+    _, threads = orc.attention(q, k, v, return_threads=True)
+    t1 = time.perf_counter() - t0
+    n = int(max(1, min(wl.T, target_seconds / max(t1, 1e-3))))
+    q, k, v = frames(n)
+    t0 = time.perf_counter()
+    orc.attention(q, k, v)
+    sec = time.perf_counter() - t0
+    fl = 4.0 * n * H * S * S * D
+    return {"value": round(fl / sec / 1e12, 6), "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d of %d frames of one spatial attention call (%s, fp64, %.1f s)" % (n, wl.T, wl.name, sec),
+            "seconds": round(sec, 2)}
+
+
+if __name__ == "__main__":
+    main()
