@@ -49,7 +49,9 @@ int launch_tile(int n_batch, int n_head, int sq, int sk, long long q_bs, long lo
   const long long n_bh = (long long)n_batch * n_head;
   const long long grid = (n_bh + 7) / 8 * 8 * p.n_qblk;
   if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "problem too large for one launch (%lld workgroups)", grid);
-  hipLaunchKernelGGL((pab::attn_tile_kernel<T, D, TILE_NQT, TILE_KB>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  constexpr bool DIRECT = sizeof(T) == 2;   // bf16 rows go from global memory straight into LDS
+  hipLaunchKernelGGL((pab::attn_tile_kernel<T, D, TILE_NQT, TILE_KB, DIRECT>), dim3((unsigned)grid), dim3(256), 0, st,
+                     p);
   return PAB_OK;
 }
 
