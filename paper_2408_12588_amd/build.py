@@ -14,6 +14,9 @@ HIPCC_FLAGS = [
     # packed fp32 VALU forms stay off for device code (the host pass does not know the
     # feature and says so; that warning is harmless)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results feed VALU code (softmax): select the VGPR form so that no accumulator has to be
+    # copied between the AGPR and VGPR halves of the register file
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wno-unused-command-line-argument",
 ]
 

@@ -1,12 +1,13 @@
 // Tiled attention kernel for long query sequences (spatial and cross attention,
 // paper Sec. 2.1): o = softmax(q k^T / sqrt(D)) v per (batch, head), computed
-// with an online softmax over blocks of keys so that scores never reach memory.
+// with an online softmax over tiles of keys so that scores never reach memory.
 //
-// Work split: one workgroup = 4 wavefronts = 128*NQT consecutive queries of one
-// (batch, head); each wavefront owns NQT tiles of 32 queries whose q fragments
-// stay in registers.  Keys and values stream through a double-buffered LDS
-// stage in blocks of KB keys, both stored row-major exactly as in memory (for
-// bf16 inputs the global loads write LDS directly, no registers in between).
+// Work split: one workgroup = 4 wavefronts (one per SIMD) = 128*NQT consecutive
+// queries of one (batch, head); each wavefront owns NQT tiles of 32 queries
+// whose q fragments stay in registers.  Keys and values stream through a ring
+// of LDS stages in blocks of 64 keys, stored row-major exactly as in memory
+// (for bf16 inputs the global loads write LDS directly, no registers in
+// between, two blocks ahead of their use).
 //
 // Per 32-key tile and 32-query tile the wavefront computes, with bf16 MFMA:
 //   S^T[key, query]  = K Q^T                (A = keys, B = queries)
@@ -16,10 +17,15 @@
 // scalar, and (with the key permutation sigma) the accumulator registers of the
 // first product are already the B operand of the second.  Row D of the V^T
 // operand (a padding row of the 32-row output tile) is forced to 1.0, so row D
-// of O^T accumulates the softmax denominator on the matrix core.  The running maximum m is only raised when some score exceeds it
-// by more than 8 in the exponent (probabilities then stay below 2^8, harmless
-// in fp32 / bf16); numerator and denominator always share the same m, so the
-// quotient is unaffected.
+// of O^T accumulates the softmax denominator on the matrix core.  The running
+// maximum m is only raised when some score exceeds it by more than 8 in the
+// exponent (probabilities then stay below 2^8, harmless in fp32 / bf16);
+// numerator and denominator always share the same m, so the quotient is
+// unaffected.
+//
+// The loop is software pipelined inside the wavefront: the scores of tile t+1
+// are issued to the matrix core before the exponentials of tile t are taken, so
+// that MFMA and VALU work of one wavefront overlap.
 #pragma once
 #include "mfma_util.hpp"
 
@@ -37,7 +43,7 @@ struct TileParams {
 // One wavefront-wide 16-byte-per-lane copy from global memory straight into LDS: lane i's 16 bytes
 // at base + voff land at LDS byte address lds_addr + 16*i (lds_addr and base are wavefront-uniform).
 // Completion is tracked by vmcnt; the compiler does not see this instruction, so the caller waits
-// (s_waitcnt vmcnt(0)) before the barrier that publishes the data.
+// (s_waitcnt vmcnt) before the barrier that publishes the data.
 __device__ __forceinline__ void dma16_to_lds(const void *base, unsigned voff, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
@@ -49,22 +55,31 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3))) *)(p));
 }
 
-template <typename T, int D, int NQT, int KB, bool DIRECT>
+// max over lanes j and j+32 (the two lanes that share a query), result in both
+__device__ __forceinline__ float max_pair(float x) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
+template <typename T, int D, int NQT, bool DIRECT>
 __global__ __launch_bounds__(256, 2) void attn_tile_kernel(const TileParams p) {
   using HD = HeadDim<D>;
   constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
-  constexpr int KT = KB / 32;        // 32-key tiles per block
+  constexpr int KB = 64;             // keys per LDS block = 2 tiles of 32
+  constexpr int NST = 4;             // LDS stages in the ring
   constexpr int QBLK = 128 * NQT;    // queries per workgroup
   constexpr int RP = D;              // row pitch of the K and V tiles in LDS: rows packed as in memory
-  constexpr int TILE_ELEMS = KB * RP, STAGE_ELEMS = 2 * TILE_ELEMS;   // K tile, then V tile
+  constexpr int TILE_ELEMS = KB * RP, STAGE_ELEMS = 2 * TILE_ELEMS;   // K rows, then V rows
   constexpr int SLACK = 64;          // fragment reads of a tile's last row run past its pitch: finite
                                      // garbage that only meets zero q columns / discarded output rows
-  constexpr int NTC = KB * CH;       // 16-byte chunks per tile; chunk c = (row c / CH, chunk c % CH)
-  static_assert(KB % 32 == 0, "key block must be a multiple of 32");
+  constexpr int NTC = KB * CH;       // 16-byte chunks per K (or V) block; chunk c = (row c / CH, chunk c % CH)
   static_assert(!DIRECT || sizeof(T) == 2, "direct-to-LDS staging needs bf16 inputs");
   static_assert(NTC % 64 == 0, "staging works in whole-wavefront rounds of 64 chunks");
+  constexpr int ROUNDS = 2 * NTC / 64;       // staging rounds per block (K rounds, then V rounds)
+  constexpr int MYR = (ROUNDS + 3) / 4;      // rounds per wavefront (the last may repeat a round)
+  static_assert(MYR < 8, "vmcnt immediates below assume few staging rounds");
 
-  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * STAGE_ELEMS + SLACK];
+  __shared__ __attribute__((aligned(16))) bf16_t smem[NST * STAGE_ELEMS + SLACK];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -88,8 +103,55 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(const TileParams p) {
   const int q_wave0 = qblk * QBLK + wave * (32 * NQT);
   const bool wave_active = q_wave0 < sq;
 
-  // ---- q fragments (B operand of the first product), kept for the whole kernel ----
-  bf16x8 qf[NQT][KSTEPS];
+  // ---- staging of key block blk into LDS stage `stage`.  The ROUNDS rounds of 64 chunks are dealt
+  //      to the 4 wavefronts round-robin.  Rows past the end of the sequence re-read the last valid
+  //      row: their scores are masked, so they carry no weight. ----
+  const int ntile = (sk + 31) >> 5;          // 32-key tiles, the last possibly partial
+  const int nkb = (ntile + 1) >> 1;          // 64-key blocks
+  const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
+
+  auto my_round = [&](int i) { const int r = wave + 4 * i; return r < ROUNDS ? r : ROUNDS - 1; };
+  auto chunk_off = [&](int i, int blk) -> long long {   // element offset of this lane's chunk, round i
+    const int round = my_round(i);
+    const int c = (round % (ROUNDS / 2)) * 64 + lane;
+    int key = blk * KB + c / CH;
+    key = key < sk ? key : sk - 1;
+    return key * (round < ROUNDS / 2 ? p.k_ss : p.v_ss) + 8 * (c % CH);
+  };
+  unsigned voff[MYR];   // byte offsets relative to the block's first K / V row (full blocks)
+#pragma unroll
+  for (int i = 0; i < MYR; ++i) voff[i] = (unsigned)(2 * chunk_off(i, 0));
+
+  auto issue = [&](int blk, int stage) {
+    const bool tail = (blk + 1) * KB > sk;
+#pragma unroll
+    for (int i = 0; i < MYR; ++i) {
+      const int round = my_round(i);
+      const bool is_k = round < ROUNDS / 2;
+      const long long blk_off = (long long)blk * KB * (is_k ? p.k_ss : p.v_ss);
+      if (DIRECT) {
+        const unsigned off = tail ? (unsigned)(2 * (chunk_off(i, blk) - blk_off)) : voff[i];
+        dma16_to_lds((is_k ? kb_ : vb) + blk_off, off, smem_addr + 2 * stage * STAGE_ELEMS + 1024 * round);
+      } else {   // element types that need conversion go through registers, synchronously
+        *reinterpret_cast<bf16x8 *>(smem + stage * STAGE_ELEMS + 512 * round + 8 * lane) =
+            Io<T>::load8((is_k ? kb_ : vb) + chunk_off(i, blk));
+      }
+    }
+  };
+  // wait until at most `blocks` of this wavefront's staged blocks are still in flight
+  auto wait_staged = [&](int blocks) {
+    if (!DIRECT) return;
+    if (blocks >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * MYR));
+    else if (blocks == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | MYR);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  };
+
+  // ---- prologue: first three blocks on their way, then the q fragments ----
+  if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + NST * STAGE_ELEMS)[tid] = 0u;   // the slack is defined
+  const int npre = nkb < 3 ? nkb : 3;
+  for (int b = 0; b < npre; ++b) issue(b, b);
+
+  bf16x8 qf[NQT][KSTEPS];   // B operand of the first product, kept for the whole kernel
 #pragma unroll
   for (int n = 0; n < NQT; ++n) {
     int qrow = q_wave0 + 32 * n + j;
@@ -100,59 +162,6 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(const TileParams p) {
       qf[n][s] = (d0 < D) ? Io<T>::load8(qb + qrow * p.q_ss + d0) : zero8();
     }
   }
-
-  // ---- staging of one key block into LDS stage `stage`.  The 2*NTC/64 rounds of 64 chunks (K tile
-  //      first, then V tile) are dealt to the 4 wavefronts round-robin.  Rows past the end of the
-  //      sequence re-read the last valid row: their scores are masked, so they carry no weight. ----
-  constexpr int ROUNDS = 2 * NTC / 64;
-  constexpr int MYR = (ROUNDS + 3) / 4;
-  const int nkb = (sk + KB - 1) / KB;
-  const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
-
-  auto chunk_off = [&](int i, int blk) -> long long {   // element offset of this lane's chunk in round wave + 4 i
-    const int round = wave + 4 * i;
-    const int c = (round % (ROUNDS / 2)) * 64 + lane;
-    int key = blk * KB + c / CH;
-    key = key < sk ? key : sk - 1;
-    return key * (round < ROUNDS / 2 ? p.k_ss : p.v_ss) + 8 * (c % CH);
-  };
-
-  bf16x8 stage_reg[DIRECT ? 1 : MYR];
-  unsigned voff[DIRECT ? MYR : 1];   // byte offsets relative to the block's first K / V row
-  if (DIRECT) {
-#pragma unroll
-    for (int i = 0; i < MYR; ++i) voff[i] = (unsigned)(2 * chunk_off(i, 0));
-  }
-  auto issue = [&](int blk, int stage) {
-    const bool tail = (blk + 1) * KB > sk;
-#pragma unroll
-    for (int i = 0; i < MYR; ++i) {
-      const int round = wave + 4 * i;
-      if (round < ROUNDS) {
-        const bool is_k = round < ROUNDS / 2;
-        if (DIRECT) {
-          const T *base = is_k ? kb_ + (long long)blk * KB * p.k_ss : vb + (long long)blk * KB * p.v_ss;
-          const unsigned off = tail ? (unsigned)(2 * (chunk_off(i, blk) - (long long)blk * KB * (is_k ? p.k_ss : p.v_ss)))
-                                    : voff[i];
-          dma16_to_lds(base, off, smem_addr + 2 * stage * STAGE_ELEMS + 1024 * round);
-        } else {
-          stage_reg[i] = Io<T>::load8((is_k ? kb_ : vb) + chunk_off(i, blk));
-        }
-      }
-    }
-  };
-  auto commit = [&](int stage) {
-    if (DIRECT) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's share of the block has landed
-    } else {
-#pragma unroll
-      for (int i = 0; i < MYR; ++i) {
-        const int round = wave + 4 * i;
-        if (round < ROUNDS)
-          *reinterpret_cast<bf16x8 *>(smem + stage * STAGE_ELEMS + 512 * round + 8 * lane) = stage_reg[i];
-      }
-    }
-  };
 
   f32x16 oacc[NQT][DT];
   float m_run[NQT];
@@ -168,120 +177,154 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(const TileParams p) {
   const float c = p.c;
   const float thr = 8.0f / c;   // raise the running maximum only past this margin (raw score units)
 
-  // per-lane fragment offsets inside a stage
-  const int k_off = sigma(j) * RP + 8 * g;                                   // + (32 kt) * RP + 16 s
+  // per-lane fragment offsets inside a tile of 32 keys
+  const int k_off = sigma(j) * RP + 8 * g;                                           // + 16 s
   const int i16 = lane & 15, q4 = lane >> 4;
-  const int v_off = TILE_ELEMS + (8 * (q4 >> 1) + (i16 >> 2)) * RP + 16 * (q4 & 1) + 4 * (i16 & 3);
-                                                                             // + (32 kt + 16 m + 4 hh) * RP + 32 dt
+  const int v_off = (8 * (q4 >> 1) + (i16 >> 2)) * RP + 16 * (q4 & 1) + 4 * (i16 & 3);   // + (16 m + 4 hh) * RP + 32 dt
   constexpr int LDT = D / 32, LLOC = D % 32;   // output tile / row that holds the softmax denominator
   const bool ones_lane = j == LLOC;
 
-  if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + 2 * STAGE_ELEMS)[tid] = 0u;   // the slack is defined
-
-  issue(0, 0);
-  commit(0);
-  __syncthreads();
-
-  for (int blk = 0; blk < nkb; ++blk) {
-    const int stage = blk & 1;
-    if (blk + 1 < nkb) issue(blk + 1, stage ^ 1);
-
-    if (wave_active) {
-      const bf16_t *st = smem + stage * STAGE_ELEMS;
+  // S^T = K Q^T for one 32-key tile
+  auto qk = [&](f32x16(&S)[NQT], const bf16_t *ktile) {
+    bf16x8 kf[KSTEPS];
 #pragma unroll
-      for (int kt = 0; kt < KT; ++kt) {
-        if (blk * KB + 32 * kt >= sk) break;   // tile entirely past the end of the sequence
-        // ---- S^T = K Q^T for this 32-key tile ----
-        f32x16 sacc[NQT];
-        bf16x8 kf[KSTEPS];
+    for (int s = 0; s < KSTEPS; ++s) kf[s] = *reinterpret_cast<const bf16x8 *>(ktile + k_off + 16 * s);
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s)
-          kf[s] = *reinterpret_cast<const bf16x8 *>(st + k_off + (32 * kt) * RP + 16 * s);
+    for (int n = 0; n < NQT; ++n)
 #pragma unroll
-        for (int n = 0; n < NQT; ++n)
+      for (int r = 0; r < 16; ++r) S[n][r] = 0.0f;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[n][r] = 0.0f;
+    for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s)
+      for (int n = 0; n < NQT; ++n) S[n] = mfma32(kf[s], qf[n][s], S[n]);
+  };
+  // first half of the online softmax: mask, tile maximum, and (rarely) raising the running maximum
+  auto track_max = [&](f32x16(&S)[NQT], int key0, bool masked) {
+    if (masked) {   // keys past the end of the sequence take no probability mass
 #pragma unroll
-          for (int n = 0; n < NQT; ++n) sacc[n] = mfma32(kf[s], qf[n][s], sacc[n]);
-
-        // keys past the end of the sequence take no probability mass
-        if (blk == nkb - 1 && blk * KB + 32 * (kt + 1) > sk) {
+      for (int r = 0; r < 16; ++r)
+        if (key0 + key_of_reg(r, g) >= sk) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = blk * KB + 32 * kt + key_of_reg(r, g);
-            if (key >= sk) {
-#pragma unroll
-              for (int n = 0; n < NQT; ++n) sacc[n][r] = -INFINITY;
-            }
-          }
+          for (int n = 0; n < NQT; ++n) S[n][r] = -INFINITY;
         }
-
-        // ---- online softmax, one query per lane (lanes j and j+32 share a query) ----
-        bf16x8 pf[NQT][2];
+    }
+    bool grow = false;
+    float mx[NQT];
 #pragma unroll
-        for (int n = 0; n < NQT; ++n) {
-          float mx = fmaxf(sacc[n][0], sacc[n][1]);
+    for (int n = 0; n < NQT; ++n) {
+      float a = fmaxf(fmaxf(S[n][0], S[n][1]), S[n][2]);
+      float b = fmaxf(fmaxf(S[n][3], S[n][4]), S[n][5]);
 #pragma unroll
-          for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sacc[n][r], sacc[n][r + 1]));
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
-          if (__builtin_amdgcn_ballot_w64(mx > m_run[n] + thr) != 0) {   // rare after the first tile
-            const float m_new = fmaxf(m_run[n], mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run[n] - m_new) * c);
-            m_run[n] = m_new;
+      for (int r = 6; r < 14; r += 4) {
+        a = fmaxf(fmaxf(a, S[n][r]), S[n][r + 1]);
+        b = fmaxf(fmaxf(b, S[n][r + 2]), S[n][r + 3]);
+      }
+      a = fmaxf(fmaxf(a, S[n][14]), S[n][15]);
+      mx[n] = max_pair(fmaxf(a, b));
+      grow |= mx[n] > m_run[n] + thr;
+    }
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {   // rare after the first tile
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+      for (int n = 0; n < NQT; ++n) {
+        const float m_new = fmaxf(m_run[n], mx[n]);
+        const float alpha = __builtin_amdgcn_exp2f((m_run[n] - m_new) * c);
+        m_run[n] = m_new;
 #pragma unroll
-              for (int r = 0; r < 16; ++r) oacc[n][dt][r] *= alpha;
-          }
-          const float mc = m_run[n] * c;
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            pf[n][r >> 3][r & 7] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[n][r], c, -mc));
-        }
-
-        // ---- O^T += V^T P^T; V^T fragments come from the row-major tile via transposing reads ----
-#pragma unroll
-        for (int m = 0; m < 2; ++m)
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            const bf16_t *vp = st + v_off + (32 * kt + 16 * m) * RP + 32 * dt;
-            const bf16x4 lo = lds_read_tr4(vp), hi = lds_read_tr4(vp + 4 * RP);
-            bf16x8 vf;
-            vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
-            vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-            if (dt == LDT) vf = ones_lane ? splat8(1.0f) : vf;   // row D of V^T := 1 (rows past D: don't care)
-#pragma unroll
-            for (int n = 0; n < NQT; ++n) oacc[n][dt] = mfma32(vf, pf[n][m], oacc[n][dt]);
-          }
+          for (int r = 0; r < 16; ++r) oacc[n][dt][r] *= alpha;
       }
     }
+  };
+  // second half: P^T = exp2(c*S^T - c*m) rounded to bf16, laid out as B operands
+  auto probs = [&](const f32x16(&S)[NQT], bf16x8(&pf)[NQT][2]) {
+#pragma unroll
+    for (int n = 0; n < NQT; ++n) {
+      const float mc = m_run[n] * c;
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        pf[n][r >> 3][r & 7] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(S[n][r], c, -mc));
+    }
+  };
+  // O^T += V^T P^T; V^T fragments come from the row-major tile via transposing reads
+  auto pv = [&](const bf16x8(&pf)[NQT][2], const bf16_t *vtile) {
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const bf16_t *vp = vtile + v_off + 16 * m * RP + 32 * dt;
+        const bf16x4 lo = lds_read_tr4(vp), hi = lds_read_tr4(vp + 4 * RP);
+        bf16x8 vf;
+        vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
+        vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+        if (dt == LDT) vf = ones_lane ? splat8(1.0f) : vf;   // row D of V^T := 1 (rows past D: don't care)
+#pragma unroll
+        for (int n = 0; n < NQT; ++n) oacc[n][dt] = mfma32(vf, pf[n][m], oacc[n][dt]);
+      }
+  };
+  auto k_tile = [&](int blk, int kt) { return smem + (blk & (NST - 1)) * STAGE_ELEMS + 32 * kt * RP; };
+  auto v_tile = [&](int blk, int kt) { return smem + (blk & (NST - 1)) * STAGE_ELEMS + TILE_ELEMS + 32 * kt * RP; };
 
-    if (blk + 1 < nkb) commit(stage ^ 1);
-    __syncthreads();   // next block visible to all; everyone is done with this one
+  wait_staged(npre - 1);   // block 0 has landed
+  __syncthreads();
+
+  f32x16 S0[NQT], S1[NQT];
+  bf16x8 pf[NQT][2];
+  if (wave_active) qk(S0, k_tile(0, 0));
+
+  // ---- full blocks: no masking, no partial tiles; tile 2b is in S0 when the iteration starts ----
+  for (int b = 0; b < nkb - 1; ++b) {
+    if (wave_active) {
+      track_max(S0, 0, false);
+      qk(S1, k_tile(b, 1));
+      probs(S0, pf);
+      pv(pf, v_tile(b, 0));
+    }
+    // block b+1 must be visible before its first tile is read; everyone is done with block b-1
+    wait_staged(b + 2 < nkb ? 1 : 0);
+    __syncthreads();
+    if (b + 3 < nkb) issue(b + 3, (b + 3) & (NST - 1));
+    if (wave_active) {
+      track_max(S1, 0, false);
+      qk(S0, k_tile(b + 1, 0));
+      probs(S1, pf);
+      pv(pf, v_tile(b, 1));
+    }
   }
+  // ---- last block: one or two tiles, the last of them possibly partial ----
+  if (wave_active) {
+    const int b = nkb - 1;
+    const bool two = 2 * b + 1 < ntile;
+    const bool ragged = (sk & 31) != 0;
+    track_max(S0, 64 * b, ragged && !two);
+    if (two) qk(S1, k_tile(b, 1));
+    probs(S0, pf);
+    pv(pf, v_tile(b, 0));
+    if (two) {
+      track_max(S1, 64 * b + 32, ragged);
+      probs(S1, pf);
+      pv(pf, v_tile(b, 1));
+    }
 
-  if (!wave_active) return;
-
-  // ---- epilogue: divide by the denominator held in row D of O^T, store ----
-  constexpr int LR = 4 * (LLOC / 8) + (LLOC % 4), LG = (LLOC / 4) & 1;
+    // ---- epilogue: divide by the denominator held in row D of O^T, store ----
+    constexpr int LR = 4 * (LLOC / 8) + (LLOC % 4), LG = (LLOC / 4) & 1;
 #pragma unroll
-  for (int n = 0; n < NQT; ++n) {
-    const float denom = __shfl(oacc[n][LDT][LR], j + 32 * LG);
-    const float inv = 1.0f / denom;
-    const int qrow = q_wave0 + 32 * n + j;
-    if (qrow < sq) {
-      T *orow = ob + qrow * p.o_ss;
+    for (int n = 0; n < NQT; ++n) {
+      const float denom = __shfl(oacc[n][LDT][LR], j + 32 * LG);
+      const float inv = 1.0f / denom;
+      const int qrow = q_wave0 + 32 * n + j;
+      if (qrow < sq) {
+        T *orow = ob + qrow * p.o_ss;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          const int d0 = 32 * dt + 8 * rq + 4 * g;
-          if (d0 < D)
-            Io<T>::store4(orow + d0, oacc[n][dt][4 * rq] * inv, oacc[n][dt][4 * rq + 1] * inv,
-                          oacc[n][dt][4 * rq + 2] * inv, oacc[n][dt][4 * rq + 3] * inv);
-        }
+          for (int rq = 0; rq < 4; ++rq) {
+            const int d0 = 32 * dt + 8 * rq + 4 * g;
+            if (d0 < D)
+              Io<T>::store4(orow + d0, oacc[n][dt][4 * rq] * inv, oacc[n][dt][4 * rq + 1] * inv,
+                            oacc[n][dt][4 * rq + 2] * inv, oacc[n][dt][4 * rq + 3] * inv);
+          }
+      }
     }
   }
 }
