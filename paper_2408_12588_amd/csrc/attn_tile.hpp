@@ -2,12 +2,13 @@
 // paper Sec. 2.1): o = softmax(q k^T / sqrt(D)) v per (batch, head), computed
 // with an online softmax over tiles of keys so that scores never reach memory.
 //
-// Work split: one workgroup = 4 wavefronts (one per SIMD) = 128*NQT consecutive
-// queries of one (batch, head); each wavefront owns NQT tiles of 32 queries
-// whose q fragments stay in registers.  Keys and values stream through a ring
-// of LDS stages in blocks of 64 keys, stored row-major exactly as in memory
-// (for bf16 inputs the global loads write LDS directly, no registers in
-// between, two blocks ahead of their use).
+// Work split: one workgroup = 4 wavefronts = 128*NQT consecutive queries of one
+// (batch, head); each wavefront owns NQT tiles of 32 queries whose q fragments
+// stay in registers.  Keys and values stream through a ring of NST LDS stages,
+// one 32-key tile per stage, stored row-major exactly as in memory (for bf16
+// inputs the global loads write LDS directly, no registers in between, NST-2
+// tiles ahead of their use).  Several workgroups share a CU, so that one
+// wavefront's LDS and barrier waits are covered by the others.
 //
 // Per 32-key tile and 32-query tile the wavefront computes, with bf16 MFMA:
 //   S^T[key, query]  = K Q^T                (A = keys, B = queries)
@@ -61,23 +62,22 @@ __device__ __forceinline__ float max_pair(float x) {
   return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
-template <typename T, int D, int NQT, bool DIRECT>
-__global__ __launch_bounds__(256, 2) void attn_tile_kernel(const TileParams p) {
+template <typename T, int D, int NQT, int NST, int MINW, bool PIPE, bool DIRECT>
+__global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p) {
   using HD = HeadDim<D>;
   constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
-  constexpr int KB = 64;             // keys per LDS block = 2 tiles of 32
-  constexpr int NST = 4;             // LDS stages in the ring
+  constexpr int KB = 32;             // keys per LDS stage = one MFMA tile
   constexpr int QBLK = 128 * NQT;    // queries per workgroup
   constexpr int RP = D;              // row pitch of the K and V tiles in LDS: rows packed as in memory
   constexpr int TILE_ELEMS = KB * RP, STAGE_ELEMS = 2 * TILE_ELEMS;   // K rows, then V rows
   constexpr int SLACK = 64;          // fragment reads of a tile's last row run past its pitch: finite
                                      // garbage that only meets zero q columns / discarded output rows
-  constexpr int NTC = KB * CH;       // 16-byte chunks per K (or V) block; chunk c = (row c / CH, chunk c % CH)
-  static_assert(!DIRECT || sizeof(T) == 2, "direct-to-LDS staging needs bf16 inputs");
-  static_assert(NTC % 64 == 0, "staging works in whole-wavefront rounds of 64 chunks");
-  constexpr int ROUNDS = 2 * NTC / 64;       // staging rounds per block (K rounds, then V rounds)
+  constexpr int NTC = KB * CH;       // 16-byte chunks per K (or V) tile; chunk c = (row c / CH, chunk c % CH)
+  constexpr int PR = (NTC + 63) / 64;        // staging rounds (64 chunks each, the last maybe partial) per K or V tile
+  constexpr int ROUNDS = 2 * PR;             // K rounds, then V rounds
   constexpr int MYR = (ROUNDS + 3) / 4;      // rounds per wavefront (the last may repeat a round)
-  static_assert(MYR < 8, "vmcnt immediates below assume few staging rounds");
+  static_assert(!DIRECT || sizeof(T) == 2, "direct-to-LDS staging needs bf16 inputs");
+  static_assert(NST >= 3 && NST <= 5 && (NST - 2) * MYR < 16, "ring depth / vmcnt immediates");
 
   __shared__ __attribute__((aligned(16))) bf16_t smem[NST * STAGE_ELEMS + SLACK];
 
@@ -103,53 +103,55 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(const TileParams p) {
   const int q_wave0 = qblk * QBLK + wave * (32 * NQT);
   const bool wave_active = q_wave0 < sq;
 
-  // ---- staging of key block blk into LDS stage `stage`.  The ROUNDS rounds of 64 chunks are dealt
-  //      to the 4 wavefronts round-robin.  Rows past the end of the sequence re-read the last valid
-  //      row: their scores are masked, so they carry no weight. ----
+  // ---- staging of key tile t into LDS stage `stage`.  The ROUNDS rounds are dealt to the 4
+  //      wavefronts round-robin.  Rows past the end of the sequence re-read the last valid row:
+  //      their scores are masked, so they carry no weight. ----
   const int ntile = (sk + 31) >> 5;          // 32-key tiles, the last possibly partial
-  const int nkb = (ntile + 1) >> 1;          // 64-key blocks
   const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
 
   auto my_round = [&](int i) { const int r = wave + 4 * i; return r < ROUNDS ? r : ROUNDS - 1; };
-  auto chunk_off = [&](int i, int blk) -> long long {   // element offset of this lane's chunk, round i
-    const int round = my_round(i);
-    const int c = (round % (ROUNDS / 2)) * 64 + lane;
-    int key = blk * KB + c / CH;
+  auto chunk_of = [&](int i) { return (my_round(i) % PR) * 64 + lane; };   // chunk index inside the K or V tile
+  auto chunk_off = [&](int i, int t) -> long long {   // element offset of this lane's chunk, round i
+    const int c = chunk_of(i);
+    int key = t * KB + c / CH;
     key = key < sk ? key : sk - 1;
-    return key * (round < ROUNDS / 2 ? p.k_ss : p.v_ss) + 8 * (c % CH);
+    return key * (my_round(i) < PR ? p.k_ss : p.v_ss) + 8 * (c % CH);
   };
-  unsigned voff[MYR];   // byte offsets relative to the block's first K / V row (full blocks)
+  unsigned voff[MYR];   // byte offsets relative to the tile's first K / V row (full tiles)
 #pragma unroll
   for (int i = 0; i < MYR; ++i) voff[i] = (unsigned)(2 * chunk_off(i, 0));
 
-  auto issue = [&](int blk, int stage) {
-    const bool tail = (blk + 1) * KB > sk;
+  auto issue = [&](int t, int stage) {
+    const bool tail = (t + 1) * KB > sk;
 #pragma unroll
     for (int i = 0; i < MYR; ++i) {
       const int round = my_round(i);
-      const bool is_k = round < ROUNDS / 2;
-      const long long blk_off = (long long)blk * KB * (is_k ? p.k_ss : p.v_ss);
-      if (DIRECT) {
-        const unsigned off = tail ? (unsigned)(2 * (chunk_off(i, blk) - blk_off)) : voff[i];
-        dma16_to_lds((is_k ? kb_ : vb) + blk_off, off, smem_addr + 2 * stage * STAGE_ELEMS + 1024 * round);
-      } else {   // element types that need conversion go through registers, synchronously
-        *reinterpret_cast<bf16x8 *>(smem + stage * STAGE_ELEMS + 512 * round + 8 * lane) =
-            Io<T>::load8((is_k ? kb_ : vb) + chunk_off(i, blk));
+      const bool is_k = round < PR;
+      const long long t_off = (long long)t * KB * (is_k ? p.k_ss : p.v_ss);
+      const int lds_elem = stage * STAGE_ELEMS + (is_k ? 0 : TILE_ELEMS) + 512 * (round % PR);
+      if (chunk_of(i) < NTC) {   // the last round of a tile is partial: lanes past the tile stay idle
+        if (DIRECT) {
+          const unsigned off = tail ? (unsigned)(2 * (chunk_off(i, t) - t_off)) : voff[i];
+          dma16_to_lds((is_k ? kb_ : vb) + t_off, off, smem_addr + 2 * lds_elem);
+        } else {   // element types that need conversion go through registers, synchronously
+          *reinterpret_cast<bf16x8 *>(smem + lds_elem + 8 * lane) = Io<T>::load8((is_k ? kb_ : vb) + chunk_off(i, t));
+        }
       }
     }
   };
-  // wait until at most `blocks` of this wavefront's staged blocks are still in flight
-  auto wait_staged = [&](int blocks) {
+  // wait until at most `tiles` of this wavefront's staged tiles are still in flight
+  auto wait_staged = [&](int tiles) {
     if (!DIRECT) return;
-    if (blocks >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * MYR));
-    else if (blocks == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | MYR);
+    if (tiles >= 3) __builtin_amdgcn_s_waitcnt(0x0F70 | (3 * MYR));
+    else if (tiles == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * MYR));
+    else if (tiles == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | MYR);
     else __builtin_amdgcn_s_waitcnt(0x0F70);
   };
 
-  // ---- prologue: first three blocks on their way, then the q fragments ----
+  // ---- prologue: first NST-1 tiles on their way, then the q fragments ----
   if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + NST * STAGE_ELEMS)[tid] = 0u;   // the slack is defined
-  const int npre = nkb < 3 ? nkb : 3;
-  for (int b = 0; b < npre; ++b) issue(b, b);
+  const int npre = ntile < NST - 1 ? ntile : NST - 1;
+  for (int t = 0; t < npre; ++t) issue(t, t);
 
   bf16x8 qf[NQT][KSTEPS];   // B operand of the first product, kept for the whole kernel
 #pragma unroll
@@ -262,50 +264,69 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(const TileParams p) {
         for (int n = 0; n < NQT; ++n) oacc[n][dt] = mfma32(vf, pf[n][m], oacc[n][dt]);
       }
   };
-  auto k_tile = [&](int blk, int kt) { return smem + (blk & (NST - 1)) * STAGE_ELEMS + 32 * kt * RP; };
-  auto v_tile = [&](int blk, int kt) { return smem + (blk & (NST - 1)) * STAGE_ELEMS + TILE_ELEMS + 32 * kt * RP; };
-
-  wait_staged(npre - 1);   // block 0 has landed
-  __syncthreads();
+  auto k_tile = [&](int t) { return smem + (t % NST) * STAGE_ELEMS; };
+  auto v_tile = [&](int t) { return smem + (t % NST) * STAGE_ELEMS + TILE_ELEMS; };
 
   f32x16 S0[NQT], S1[NQT];
   bf16x8 pf[NQT][2];
-  if (wave_active) qk(S0, k_tile(0, 0));
 
-  // ---- full blocks: no masking, no partial tiles; tile 2b is in S0 when the iteration starts ----
-  for (int b = 0; b < nkb - 1; ++b) {
-    if (wave_active) {
-      track_max(S0, 0, false);
-      qk(S1, k_tile(b, 1));
-      probs(S0, pf);
-      pv(pf, v_tile(b, 0));
-    }
-    // block b+1 must be visible before its first tile is read; everyone is done with block b-1
-    wait_staged(b + 2 < nkb ? 1 : 0);
+  if (PIPE) {
+    // One pipeline step on a full (unmasked) tile t whose scores are in Sc: make tile t+1 visible,
+    // refill the stage that tile t-1 occupied, issue the scores of tile t+1 into Sn, finish tile t.
+    auto step = [&](int t, f32x16(&Sc)[NQT], f32x16(&Sn)[NQT]) {
+      const int ahead = ntile - 2 - t;                 // staged tiles beyond t+1
+      wait_staged(ahead < NST - 3 ? ahead : NST - 3);  // tile t+1 has landed (this wavefront's share)
+      __syncthreads();                                 // ... everyone's share; all are done with tile t-1
+      if (t + NST - 1 < ntile) issue(t + NST - 1, (t + NST - 1) % NST);
+      if (wave_active) {
+        track_max(Sc, 0, false);
+        qk(Sn, k_tile(t + 1));
+        probs(Sc, pf);
+        pv(pf, v_tile(t));
+      }
+    };
+
+    wait_staged(npre - 1);   // tile 0 has landed
     __syncthreads();
-    if (b + 3 < nkb) issue(b + 3, (b + 3) & (NST - 1));
-    if (wave_active) {
-      track_max(S1, 0, false);
-      qk(S0, k_tile(b + 1, 0));
-      probs(S1, pf);
-      pv(pf, v_tile(b, 1));
+    if (wave_active) qk(S0, k_tile(0));
+
+    int t = 0;
+    for (; t + 2 < ntile; t += 2) {
+      step(t, S0, S1);
+      step(t + 1, S1, S0);
+    }
+    // one or two tiles are left; the last of all may be partial
+    const bool ragged = (sk & 31) != 0;
+    if (t + 1 < ntile) {
+      step(t, S0, S1);
+      if (wave_active) {
+        track_max(S1, 32 * (t + 1), ragged);
+        probs(S1, pf);
+        pv(pf, v_tile(t + 1));
+      }
+    } else if (wave_active) {
+      track_max(S0, 32 * t, ragged);
+      probs(S0, pf);
+      pv(pf, v_tile(t));
+    }
+  } else {
+    // Unpipelined variant: each tile is scored, normalised and accumulated in turn; overlap of
+    // MFMA and VALU work then comes from the other wavefronts on the SIMD.
+    for (int t = 0; t < ntile; ++t) {
+      const int ahead = ntile - 1 - t;                 // staged tiles beyond t
+      wait_staged(ahead < NST - 2 ? ahead : NST - 2);  // tile t has landed (this wavefront's share)
+      __syncthreads();                                 // ... everyone's share; all are done with tile t-1
+      if (t + NST - 1 < ntile) issue(t + NST - 1, (t + NST - 1) % NST);
+      if (wave_active) {
+        qk(S0, k_tile(t));
+        track_max(S0, 32 * t, t == ntile - 1 && (sk & 31) != 0);
+        probs(S0, pf);
+        pv(pf, v_tile(t));
+      }
     }
   }
-  // ---- last block: one or two tiles, the last of them possibly partial ----
-  if (wave_active) {
-    const int b = nkb - 1;
-    const bool two = 2 * b + 1 < ntile;
-    const bool ragged = (sk & 31) != 0;
-    track_max(S0, 64 * b, ragged && !two);
-    if (two) qk(S1, k_tile(b, 1));
-    probs(S0, pf);
-    pv(pf, v_tile(b, 0));
-    if (two) {
-      track_max(S1, 64 * b + 32, ragged);
-      probs(S1, pf);
-      pv(pf, v_tile(b, 1));
-    }
 
+  if (wave_active) {
     // ---- epilogue: divide by the denominator held in row D of O^T, store ----
     constexpr int LR = 4 * (LLOC / 8) + (LLOC % 4), LG = (LLOC / 4) & 1;
 #pragma unroll
