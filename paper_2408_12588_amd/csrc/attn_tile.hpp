@@ -164,6 +164,9 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
       qf[n][s] = (d0 < D) ? Io<T>::load8(qb + qrow * p.q_ss + d0) : zero8();
     }
   }
+  // Drain the q loads here, outside the loop.  The compiler cannot see the staging loads, so a
+  // wait it placed inside the loop for these registers would also wait for tiles staged ahead.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
 
   f32x16 oacc[NQT][DT];
   float m_run[NQT];
