@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--kind-reps", type=int, default=40, help="launches per kind in the per-kind section")
+    ap.add_argument("--profile-kind", default=None, choices=["spatial", "temporal", "cross"],
+                    help="counter-collection mode: one 1 GiB device copy (calibration), then --kind-reps launches "
+                         "of this kind over the rotating pool; prints no result line")
     return ap.parse_args()
 
 
@@ -118,6 +121,18 @@ def main():
         return time.perf_counter() - t0, flops, launches
 
     # ---- PAB schedule: warmup, then the timed region ----
+    if args.profile_kind:
+        kind = W.KIND_NAMES.index(args.profile_kind)
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)   # 1 GiB
+        b = torch.empty_like(a)
+        b.copy_(a)                                  # reads 1 GiB, writes 1 GiB: scale for FETCH_SIZE / WRITE_SIZE
+        out = torch.empty(full, device=dev, dtype=dt)
+        for i in range(args.kind_reps):
+            pab.pab_attention_compute(kind, *inputs(i, kind), out=out)
+        torch.cuda.synchronize()
+        print("profiled %d launches of %s on %s" % (args.kind_reps, args.profile_kind, wl.name))
+        return
+
     ctx = pab.PabContext(pab.config_of(wl), dev)
     run_steps(ctx, 0, Wm)
     events = []

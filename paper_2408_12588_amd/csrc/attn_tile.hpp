@@ -24,9 +24,10 @@
 // numerator and denominator always share the same m, so the quotient is
 // unaffected.
 //
-// The loop is software pipelined inside the wavefront: the scores of tile t+1
-// are issued to the matrix core before the exponentials of tile t are taken, so
-// that MFMA and VALU work of one wavefront overlap.
+// PIPE selects a variant that is software pipelined inside the wavefront (the
+// scores of tile t+1 are issued to the matrix core before the exponentials of
+// tile t are taken).  It needs twice the score registers and measured no
+// faster than letting the other wavefronts of the SIMD provide the overlap.
 #pragma once
 #include "mfma_util.hpp"
 
@@ -40,27 +41,6 @@ struct TileParams {
   float c;        // log2(e) / sqrt(D)
   int n_qblk;     // query blocks per (batch, head)
 };
-
-// One wavefront-wide 16-byte-per-lane copy from global memory straight into LDS: lane i's 16 bytes
-// at base + voff land at LDS byte address lds_addr + 16*i (lds_addr and base are wavefront-uniform).
-// Completion is tracked by vmcnt; the compiler does not see this instruction, so the caller waits
-// (s_waitcnt vmcnt) before the barrier that publishes the data.
-__device__ __forceinline__ void dma16_to_lds(const void *base, unsigned voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(voff), "s"(base), "s"(lds_addr)
-               : "memory");
-}
-
-__device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3))) *)(p));
-}
-
-// max over lanes j and j+32 (the two lanes that share a query), result in both
-__device__ __forceinline__ float max_pair(float x) {
-  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-}
 
 template <typename T, int D, int NQT, int NST, int MINW, bool PIPE, bool DIRECT>
 __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p) {

@@ -70,6 +70,28 @@ __device__ __forceinline__ bf16x8 splat8(float x) {
   return z;
 }
 
+// One wavefront-wide 16-byte-per-lane copy from global memory straight into LDS: lane i's 16 bytes
+// at base + voff land at LDS byte address lds_addr + 16*i (lds_addr and base are wavefront-uniform).
+// Completion is tracked by vmcnt; the compiler does not see this instruction, so the caller waits
+// (s_waitcnt vmcnt) before the barrier that publishes the data.
+__device__ __forceinline__ void dma16_to_lds(const void *base, unsigned voff, unsigned lds_addr) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);   // uniform by contract; tell the compiler
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(base), "s"(lds_addr)
+               : "memory");
+}
+
+__device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3))) *)(p));
+}
+
+// max over lanes j and j+32 (the two lanes that share a query), result in both
+__device__ __forceinline__ float max_pair(float x) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
 // Head-dim dependent tile constants.
 template <int D> struct HeadDim {
   static_assert(D % 8 == 0, "head dim must be a multiple of 8");

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/pab.h"
+#include "attn_cross.hpp"
 #include "attn_temporal.hpp"
 #include "attn_tile.hpp"
 
@@ -83,6 +84,29 @@ int launch_temporal(int T_, int S, int H, const void *q, const void *k, const vo
   return PAB_OK;
 }
 
+// Cross attention with few keys and bf16 rows: K and V stay in LDS, q and o stream.
+template <int D>
+int launch_cross(int n_tok, int L, int H, const void *q, const void *k, const void *v, void *o, hipStream_t st) {
+  pab::CrossParams p;
+  p.q = q; p.k = k; p.v = v; p.o = o;
+  p.n_tok = n_tok; p.L = L; p.n_head = H;
+  p.c = (float)(1.4426950408889634 / std::sqrt((double)D));
+  const int ntile = (n_tok + 31) / 32;
+  int per_head = 512 / H;                       // about two workgroups per CU in total
+  const int cap = (ntile + 3) / 4;              // no more wavefronts than tiles
+  if (per_head > cap) per_head = cap;
+  if (per_head < 1) per_head = 1;
+  p.wg_per_head = per_head;
+  const dim3 grid((unsigned)(H * per_head)), block(256);
+  switch ((L + 31) / 32) {
+    case 1: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 1>), grid, block, 0, st, p); break;
+    case 2: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 2>), grid, block, 0, st, p); break;
+    case 3: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 3>), grid, block, 0, st, p); break;
+    default: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 4>), grid, block, 0, st, p); break;
+  }
+  return PAB_OK;
+}
+
 template <typename T, int D>
 int launch_kind(int kind, int T_, int S, int L, int H, const void *q, const void *k, const void *v, void *o,
                 hipStream_t st) {
@@ -95,6 +119,7 @@ int launch_kind(int kind, int T_, int S, int L, int H, const void *q, const void
     default: {          // cross: every video token against the L text tokens
       const long long tok = (long long)T_ * S;
       if (tok > 0x7fffffffLL) return fail(PAB_EINVAL, "too many tokens");
+      if (sizeof(T) == 2 && L <= 128 && H <= 512) return launch_cross<D>((int)tok, L, H, q, k, v, o, st);
       return launch_tile<T, D>(1, H, (int)tok, L, 0, row, 0, row, q, k, v, o, st);
     }
   }

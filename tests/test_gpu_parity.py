@@ -60,6 +60,11 @@ SHAPES = [
     (W.CROSS, 1, 70, 1, 2, 72, "bf16"),        # one text key: output = its value
     (W.CROSS, 4, 64, 16, 4, 32, "f32"),        # Tiny
     (W.CROSS, 2, 129, 64, 1, 72, "f32"),
+    (W.CROSS, 5, 101, 128, 3, 72, "bf16"),     # exactly four key tiles, ragged token tail, odd head count
+    (W.CROSS, 1, 31, 33, 16, 72, "bf16"),      # fewer tokens than one tile, one key past a tile edge
+    (W.CROSS, 7, 333, 97, 8, 72, "bf16"),      # many tiles per wavefront, heads spread over the XCDs
+    (W.CROSS, 3, 200, 60, 2, 32, "bf16"),
+    (W.CROSS, 2, 150, 129, 2, 72, "bf16"),     # one key too many for the LDS-resident kernel: tiled fallback
 ]
 
 
