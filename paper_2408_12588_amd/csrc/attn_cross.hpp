@@ -3,15 +3,18 @@
 // keys and values fit in LDS once and for all, the softmax needs a single pass,
 // and the operation is bound by streaming q in and o out of HBM.
 //
-// One workgroup = 4 wavefronts serves one head: it stages that head's K and V
+// One workgroup = NW wavefronts serves one head: it stages that head's K and V
 // rows ([L, D], row-major as in memory) into LDS once, then each wavefront walks
 // over 32-query tiles of the head with a stride of all wavefronts serving it.
 // The wavefronts never synchronise with each other after the K/V load.
 //
 // Per tile a wavefront
 //   - has the tile's 32 q rows copied global -> LDS by direct loads that were
-//     issued one tile ahead (two per-wavefront buffers), 16 bytes per lane with
-//     consecutive lanes on consecutive chunks of a row;
+//     issued two tiles ahead (three per-wavefront buffers), 16 bytes per lane
+//     with consecutive lanes on consecutive chunks of a row.  Two tiles, not
+//     one: loads and stores share one in-order-per-kind counter, and with two
+//     tiles of loads behind it a tile can be waited for without also waiting
+//     for the stores of the tile before it;
 //   - computes S^T = K Q^T for all keys (bf16 MFMA, keys x queries, so the
 //     softmax statistics are per-lane scalars), one max, P^T = exp2(c(S^T - m))
 //     in registers, O^T = V^T P^T with V^T read transposed from LDS and the
@@ -31,9 +34,10 @@ struct CrossParams {
   float c;             // log2(e) / sqrt(D)
 };
 
-// LT: 32-key tiles that hold L (1..4).
-template <int D, int LT>
-__global__ __launch_bounds__(256, 2) void attn_cross_kernel(const CrossParams p) {
+// LT: 32-key tiles that hold L (1..4).  NW: wavefronts per workgroup.  NB: q/o tile buffers per
+// wavefront (2 or 3); q tiles are requested NB-1 tiles ahead.
+template <int D, int LT, int NW, int NB>
+__global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p) {
   using HD = HeadDim<D>;
   using T = bf16_t;
   constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
@@ -45,9 +49,9 @@ __global__ __launch_bounds__(256, 2) void attn_cross_kernel(const CrossParams p)
   constexpr int QR = (32 * CH + 63) / 64;   // staging rounds for a q tile (the last may be partial)
   constexpr int SLACK = 64;
   static_assert(LT >= 1 && LT <= 4, "keys must fit four 32-key tiles");
-  static_assert(QR < 8, "vmcnt immediate");
+  static_assert((NB == 2 || NB == 3) && 2 * QR < 16, "buffers / vmcnt immediate");
 
-  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * KV_ELEMS + 4 * 2 * QB_ELEMS + SLACK];
+  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * KV_ELEMS + NW * NB * QB_ELEMS + SLACK];
   bf16_t *Ks = smem, *Vs = smem + KV_ELEMS;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -55,17 +59,26 @@ __global__ __launch_bounds__(256, 2) void attn_cross_kernel(const CrossParams p)
   const int j = lane & 31, g = lane >> 5;
   const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
 
-  // Workgroup ids go round-robin over the 8 XCDs: give an XCD neighbouring heads, whose rows share
-  // cache lines, and let all workgroups of a head walk the tokens in the same order.
+  // Workgroup ids go round-robin over the 8 XCDs.  An XCD takes one contiguous eighth of the tokens
+  // for all heads, so that the cache lines shared by neighbouring heads (rows are D elements, not
+  // a multiple of the line) are used up inside one L2.  The host makes wg_per_head a multiple of 8
+  // whenever there are enough tiles; otherwise the split is plain round-robin.
   const int H = p.n_head;
-  int head, part;
-  if ((H & 7) == 0) {
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, hpx = H >> 3;
-    head = xcd * hpx + slot % hpx;
-    part = slot / hpx;
+  const int ntile = (p.n_tok + 31) >> 5;
+  int head, t_lo, t_hi, part, parts;
+  if ((p.wg_per_head & 7) == 0) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    head = slot % H;
+    part = slot / H;
+    parts = p.wg_per_head >> 3;
+    t_lo = (int)((long long)ntile * xcd / 8);
+    t_hi = (int)((long long)ntile * (xcd + 1) / 8);
   } else {
     head = blockIdx.x % H;
     part = blockIdx.x / H;
+    parts = p.wg_per_head;
+    t_lo = 0;
+    t_hi = ntile;
   }
   const long long row = (long long)H * D;   // token stride, elements
   const T *qh = reinterpret_cast<const T *>(p.q) + (long long)head * D;
@@ -73,12 +86,11 @@ __global__ __launch_bounds__(256, 2) void attn_cross_kernel(const CrossParams p)
   const T *vh = reinterpret_cast<const T *>(p.v) + (long long)head * D;
   T *oh = reinterpret_cast<T *>(p.o) + (long long)head * D;
   const int n_tok = p.n_tok, L = p.L;
-  const int ntile = (n_tok + 31) >> 5;
-  const int stride = p.wg_per_head * 4;
-  bf16_t *qbuf = smem + 2 * KV_ELEMS + wave * (2 * QB_ELEMS);
+  const int stride = parts * NW;
+  bf16_t *qbuf = smem + 2 * KV_ELEMS + wave * (NB * QB_ELEMS);
 
   // ---- K and V of the head: KVR rounds each, dealt round-robin to the wavefronts ----
-  for (int r = wave; r < 2 * KVR; r += 4) {
+  for (int r = wave; r < 2 * KVR; r += NW) {
     const bool is_k = r < KVR;
     const int c = (r % KVR) * 64 + lane;
     if (c < LP * CH) {
@@ -88,7 +100,7 @@ __global__ __launch_bounds__(256, 2) void attn_cross_kernel(const CrossParams p)
                    smem_addr + 2 * ((is_k ? 0 : KV_ELEMS) + 512 * (r % KVR)));
     }
   }
-  if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + 2 * KV_ELEMS + 8 * QB_ELEMS)[tid] = 0u;
+  if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + 2 * KV_ELEMS + NB * NW * QB_ELEMS)[tid] = 0u;
 
   // ---- q tile t -> this wavefront's buffer `b`: QR direct loads, rows past the end repeat the last.
   //      Token offsets can exceed 32 bits: the base moves with the tile, the lane offset stays small. ----
@@ -106,9 +118,12 @@ __global__ __launch_bounds__(256, 2) void attn_cross_kernel(const CrossParams p)
     }
   };
 
-  int t = part * 4 + wave;
-  if (t < ntile) stage_q(t, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // K, V (this wavefront's share) and the first q tile have landed
+  constexpr int PD = NB - 1;   // prefetch distance in tiles
+  int t = t_lo + part * NW + wave;
+#pragma unroll
+  for (int d = 0; d < PD; ++d)
+    if (t + d * stride < t_hi) stage_q(t + d * stride, d);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // K, V (this wavefront's share) and the first q tiles have landed
   __syncthreads();                      // ... everyone's share of K and V
 
   const float c = p.c;
@@ -119,18 +134,19 @@ __global__ __launch_bounds__(256, 2) void attn_cross_kernel(const CrossParams p)
   constexpr int LR = 4 * (LLOC / 8) + (LLOC % 4), LG = (LLOC / 4) & 1;
   const bool ones_lane = j == LLOC;
 
-  for (int it = 0; t < ntile; t += stride, ++it) {
-    const int cur = it & 1;
+  int cur = 0;   // ring position of tile t's buffer
+  for (; t < t_hi; t += stride, cur = cur == NB - 1 ? 0 : cur + 1) {
     bf16_t *qb = qbuf + cur * QB_ELEMS;
-    const int tn = t + stride;
-    if (tn < ntile) {
-      stage_q(tn, cur ^ 1);
-      // loads complete in order: with at most QR operations in flight, tile t's loads (issued before
-      // the previous tile's stores and before these QR loads) are done
-      __builtin_amdgcn_s_waitcnt(0x0F70 | QR);
-    } else {
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-    }
+    // Request the tile PD tiles ahead into the buffer the previous tile was written out from, then
+    // wait for tile t.  Loads complete in order among themselves (so do stores, but not against
+    // loads): tile t's loads are followed by those of the `later` tiles already requested, so once at
+    // most later*QR operations are in flight tile t has landed, whatever earlier stores are doing.
+    if (t + PD * stride < t_hi) stage_q(t + PD * stride, cur == 0 ? NB - 1 : cur - 1);
+    const int left = (t_hi - 1 - t) / stride;
+    const int later = left < PD ? left : PD;
+    if (later >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * QR));
+    else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | QR);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     // ---- q fragments (B operand): query j, columns 16 s + 8 g; columns past D are zero ----

@@ -85,6 +85,9 @@ int launch_temporal(int T_, int S, int H, const void *q, const void *k, const vo
 }
 
 // Cross attention with few keys and bf16 rows: K and V stay in LDS, q and o stream.
+constexpr int CROSS_NW = 4;    // wavefronts per workgroup
+constexpr int CROSS_NB = 2;    // q/o tile buffers per wavefront (two workgroups fit a CU's LDS)
+
 template <int D>
 int launch_cross(int n_tok, int L, int H, const void *q, const void *k, const void *v, void *o, hipStream_t st) {
   pab::CrossParams p;
@@ -92,17 +95,18 @@ int launch_cross(int n_tok, int L, int H, const void *q, const void *k, const vo
   p.n_tok = n_tok; p.L = L; p.n_head = H;
   p.c = (float)(1.4426950408889634 / std::sqrt((double)D));
   const int ntile = (n_tok + 31) / 32;
-  int per_head = 512 / H;                       // about two workgroups per CU in total
-  const int cap = (ntile + 3) / 4;              // no more wavefronts than tiles
-  if (per_head > cap) per_head = cap;
+  // about two workgroups per CU in total; a multiple of 8 per head lets every XCD take its own
+  // eighth of the tokens; never more wavefronts than tiles
+  int per_head = (512 / H + 7) / 8 * 8;
+  if (ntile < per_head * CROSS_NW) per_head = (ntile + CROSS_NW - 1) / CROSS_NW;
   if (per_head < 1) per_head = 1;
   p.wg_per_head = per_head;
-  const dim3 grid((unsigned)(H * per_head)), block(256);
+  const dim3 grid((unsigned)(H * per_head)), block(64 * CROSS_NW);
   switch ((L + 31) / 32) {
-    case 1: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 1>), grid, block, 0, st, p); break;
-    case 2: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 2>), grid, block, 0, st, p); break;
-    case 3: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 3>), grid, block, 0, st, p); break;
-    default: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 4>), grid, block, 0, st, p); break;
+    case 1: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 1, CROSS_NW, CROSS_NB>), grid, block, 0, st, p); break;
+    case 2: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 2, CROSS_NW, CROSS_NB>), grid, block, 0, st, p); break;
+    case 3: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 3, CROSS_NW, CROSS_NB>), grid, block, 0, st, p); break;
+    default: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 4, CROSS_NW, CROSS_NB>), grid, block, 0, st, p); break;
   }
   return PAB_OK;
 }
