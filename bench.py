@@ -29,6 +29,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM bytes per launch of the dominant (spatial) kernel, from the rocprofv3 --pmc runs summarised in
+# profiles/attn_kernels_<workload>_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scales
+# a 1 GiB copy gives).  Not measured live: counters need the profiler.  None where no profile exists.
+PROFILED_SPATIAL_TRAFFIC_BYTES = {"opensora_480p": 395.6e6}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -174,7 +179,9 @@ def main():
         achieved = wl.flops(W.SPATIAL) / (avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "attn_tile_kernel (spatial)", "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None, "avg_launch_ms": round(avg_ms, 4), "launches": len(spatial_ms),
+                    "traffic": PROFILED_SPATIAL_TRAFFIC_BYTES.get(wl.name),
+                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
+                    "algorithmic_bytes": wl.bytes(W.SPATIAL), "avg_launch_ms": round(avg_ms, 4), "launches": len(spatial_ms),
                     "flops_per_launch": wl.flops(W.SPATIAL)}
     else:
         roofline = None
@@ -224,13 +231,16 @@ def cpu_baseline(wl, target_seconds):
     _, threads = orc.attention(q, k, v, return_threads=True)
     t1 = time.perf_counter() - t0
     n = int(max(1, min(wl.T, target_seconds / max(t1, 1e-3))))
+    reps = int(max(1, target_seconds / max(t1 * n, 1e-3)))
     q, k, v = frames(n)
     t0 = time.perf_counter()
-    orc.attention(q, k, v)
+    for _ in range(reps):
+        orc.attention(q, k, v)
     sec = time.perf_counter() - t0
-    fl = 4.0 * n * H * S * S * D
+    fl = 4.0 * n * H * S * S * D * reps
     return {"value": round(fl / sec / 1e12, 6), "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d of %d frames of one spatial attention call (%s, fp64, %.1f s)" % (n, wl.T, wl.name, sec),
+            "sample": "%d of %d frames of one spatial attention call, %d times (%s, fp64, %.1f s)"
+                      % (n, wl.T, reps, wl.name, sec),
             "seconds": round(sec, 2)}
 
 
