@@ -17,6 +17,8 @@ HIPCC_FLAGS = [
     # MFMA results feed VALU code (softmax): select the VGPR form so that no accumulator has to be
     # copied between the AGPR and VGPR halves of the register file
     "-mllvm", "-amdgpu-mfma-vgpr-form",
+    # no NaN bookkeeping in max chains (masked scores are -inf, never NaN)
+    "-fno-honor-nans",
     "-Wno-unused-command-line-argument",
 ]
 

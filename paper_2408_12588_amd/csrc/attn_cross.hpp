@@ -17,8 +17,9 @@
 //     for the stores of the tile before it;
 //   - computes S^T = K Q^T for all keys (bf16 MFMA, keys x queries, so the
 //     softmax statistics are per-lane scalars), one max, P^T = exp2(c(S^T - m))
-//     in registers, O^T = V^T P^T with V^T read transposed from LDS and the
-//     softmax denominator accumulated by an all-ones row of V^T;
+//     in registers, O^T = V^T P^T with V^T read transposed from LDS; V rows in
+//     LDS carry an extra chunk {1, 0, ..}, so row D of O^T is the softmax
+//     denominator, accumulated on the matrix core;
 //   - writes the normalised tile into the LDS buffer its q rows came from and
 //     from there to global memory, again whole rows per instruction.
 #pragma once
@@ -43,16 +44,18 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
   constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
   constexpr int LP = 32 * LT;               // key rows held in LDS (rows past L repeat row L-1, masked)
   constexpr int RP = D;                     // row pitch: rows packed as in memory
-  constexpr int KV_ELEMS = LP * RP;         // one of K, V
+  constexpr int VCH = CH + 1, VP = 8 * VCH; // V rows in LDS: CH data chunks, then the constant chunk {1, 0, ..}
+  constexpr int K_ELEMS = LP * RP, V_ELEMS = LP * VP, KV_ELEMS = K_ELEMS + V_ELEMS;
   constexpr int QB_ELEMS = 32 * RP;         // one q / o tile buffer
-  constexpr int KVR = (LP * CH + 63) / 64;  // staging rounds for K (and for V)
+  constexpr int KR = (LP * CH + 63) / 64;   // staging rounds (64 chunk slots) for K
+  constexpr int VR = (LP * VCH + 63) / 64;  // ... for V (the slots of the constant chunks stay idle)
   constexpr int QR = (32 * CH + 63) / 64;   // staging rounds for a q tile (the last may be partial)
   constexpr int SLACK = 64;
   static_assert(LT >= 1 && LT <= 4, "keys must fit four 32-key tiles");
   static_assert((NB == 2 || NB == 3) && 2 * QR < 16, "buffers / vmcnt immediate");
 
-  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * KV_ELEMS + NW * NB * QB_ELEMS + SLACK];
-  bf16_t *Ks = smem, *Vs = smem + KV_ELEMS;
+  __shared__ __attribute__((aligned(16))) bf16_t smem[KV_ELEMS + NW * NB * QB_ELEMS + SLACK];
+  bf16_t *Ks = smem, *Vs = smem + K_ELEMS;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -87,20 +90,25 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
   T *oh = reinterpret_cast<T *>(p.o) + (long long)head * D;
   const int n_tok = p.n_tok, L = p.L;
   const int stride = parts * NW;
-  bf16_t *qbuf = smem + 2 * KV_ELEMS + wave * (NB * QB_ELEMS);
+  bf16_t *qbuf = smem + KV_ELEMS + wave * (NB * QB_ELEMS);
 
-  // ---- K and V of the head: KVR rounds each, dealt round-robin to the wavefronts ----
-  for (int r = wave; r < 2 * KVR; r += NW) {
-    const bool is_k = r < KVR;
-    const int c = (r % KVR) * 64 + lane;
-    if (c < LP * CH) {
-      int key = c / CH;
+  // ---- K and V of the head, rounds dealt round-robin to the wavefronts ----
+  for (int r = wave; r < KR + VR; r += NW) {
+    const bool is_k = r < KR;
+    const int c = (is_k ? r : r - KR) * 64 + lane, per = is_k ? CH : VCH;
+    if (c < LP * per && c % per < CH) {
+      int key = c / per;
       key = key < L ? key : L - 1;
-      dma16_to_lds(is_k ? kh : vh, (unsigned)(2 * (key * row + 8 * (c % CH))),
-                   smem_addr + 2 * ((is_k ? 0 : KV_ELEMS) + 512 * (r % KVR)));
+      dma16_to_lds(is_k ? kh : vh, (unsigned)(2 * (key * row + 8 * (c % per))),
+                   smem_addr + 2 * (is_k ? 512 * r : K_ELEMS + 512 * (r - KR)));
     }
   }
-  if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + 2 * KV_ELEMS + NB * NW * QB_ELEMS)[tid] = 0u;
+  for (int idx = tid; idx < LP; idx += 64 * NW) {   // constant chunk of every V row
+    bf16x8 one = zero8();
+    one[0] = (bf16_t)1.0f;
+    *reinterpret_cast<bf16x8 *>(Vs + idx * VP + D) = one;
+  }
+  if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + KV_ELEMS + NB * NW * QB_ELEMS)[tid] = 0u;
 
   // ---- q tile t -> this wavefront's buffer `b`: QR direct loads, rows past the end repeat the last.
   //      Token offsets can exceed 32 bits: the base moves with the tile, the lane offset stays small. ----
@@ -129,10 +137,9 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
   const float c = p.c;
   const int k_off = sigma(j) * RP + 8 * g;                                             // + 32 kt * RP + 16 s
   const int i16 = lane & 15, q4 = lane >> 4;
-  const int v_off = (8 * (q4 >> 1) + (i16 >> 2)) * RP + 16 * (q4 & 1) + 4 * (i16 & 3);   // + (32 kt + 16 m + 4 hh) * RP + 32 dt
+  const int v_off = (8 * (q4 >> 1) + (i16 >> 2)) * VP + 16 * (q4 & 1) + 4 * (i16 & 3);   // + (32 kt + 16 m + 4 hh) * VP + 32 dt
   constexpr int LDT = D / 32, LLOC = D % 32;
   constexpr int LR = 4 * (LLOC / 8) + (LLOC % 4), LG = (LLOC / 4) & 1;
-  const bool ones_lane = j == LLOC;
 
   int cur = 0;   // ring position of tile t's buffer
   for (; t < t_hi; t += stride, cur = cur == NB - 1 ? 0 : cur + 1) {
@@ -209,12 +216,11 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
       for (int m = 0; m < 2; ++m)
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-          const bf16_t *vp = Vs + v_off + (32 * kt + 16 * m) * RP + 32 * dt;
-          const bf16x4 lo = lds_read_tr4(vp), hi = lds_read_tr4(vp + 4 * RP);
+          const bf16_t *vp = Vs + v_off + (32 * kt + 16 * m) * VP + 32 * dt;
+          const bf16x4 lo = lds_read_tr4(vp), hi = lds_read_tr4(vp + 4 * VP);
           bf16x8 vf;
           vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
           vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-          if (dt == LDT) vf = ones_lane ? splat8(1.0f) : vf;   // row D of V^T := 1 -> softmax denominator
           oacc[dt] = mfma32(vf, pf[m], oacc[dt]);
         }
     }

@@ -16,9 +16,10 @@
 //   O^T[d, query]   += V^T P^T              (A = values read transposed, B = P^T)
 // Keeping the query on the lane axis makes every softmax statistic a per-lane
 // scalar, and (with the key permutation sigma) the accumulator registers of the
-// first product are already the B operand of the second.  Row D of the V^T
-// operand (a padding row of the 32-row output tile) is forced to 1.0, so row D
-// of O^T accumulates the softmax denominator on the matrix core.  The running
+// first product are already the B operand of the second.  V rows in LDS carry
+// one extra 16-byte chunk {1, 0, ..} after their D values (written once; the
+// staging loads skip it), so row D of V^T is all ones and row D of O^T
+// accumulates the softmax denominator on the matrix core.  The running
 // maximum m is only raised when some score exceeds it by more than 8 in the
 // exponent (probabilities then stay below 2^8, harmless in fp32 / bf16);
 // numerator and denominator always share the same m, so the quotient is
@@ -48,13 +49,16 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
   constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
   constexpr int KB = 32;             // keys per LDS stage = one MFMA tile
   constexpr int QBLK = 128 * NQT;    // queries per workgroup
-  constexpr int RP = D;              // row pitch of the K and V tiles in LDS: rows packed as in memory
-  constexpr int TILE_ELEMS = KB * RP, STAGE_ELEMS = 2 * TILE_ELEMS;   // K rows, then V rows
+  constexpr int RP = D;              // row pitch of the K tile in LDS: rows packed as in memory
+  constexpr int VCH = CH + 1;        // chunks per V row in LDS: CH of data, then the constant chunk {1, 0, ..}
+  constexpr int VP = 8 * VCH;        // row pitch of the V tile
+  constexpr int TILE_ELEMS = KB * RP;                       // K rows ...
+  constexpr int STAGE_ELEMS = TILE_ELEMS + KB * VP;         // ... then V rows
   constexpr int SLACK = 64;          // fragment reads of a tile's last row run past its pitch: finite
                                      // garbage that only meets zero q columns / discarded output rows
-  constexpr int NTC = KB * CH;       // 16-byte chunks per K (or V) tile; chunk c = (row c / CH, chunk c % CH)
-  constexpr int PR = (NTC + 63) / 64;        // staging rounds (64 chunks each, the last maybe partial) per K or V tile
-  constexpr int ROUNDS = 2 * PR;             // K rounds, then V rounds
+  constexpr int PRK = (KB * CH + 63) / 64;   // staging rounds (64 chunk slots each, the last maybe partial) of the K tile
+  constexpr int PRV = (KB * VCH + 63) / 64;  // ... of the V tile (the slots of the constant chunks stay idle)
+  constexpr int ROUNDS = PRK + PRV;          // K rounds, then V rounds
   constexpr int MYR = (ROUNDS + 3) / 4;      // rounds per wavefront (the last may repeat a round)
   static_assert(!DIRECT || sizeof(T) == 2, "direct-to-LDS staging needs bf16 inputs");
   static_assert(NST >= 3 && NST <= 5 && (NST - 2) * MYR < 16, "ring depth / vmcnt immediates");
@@ -90,12 +94,18 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
   const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
 
   auto my_round = [&](int i) { const int r = wave + 4 * i; return r < ROUNDS ? r : ROUNDS - 1; };
-  auto chunk_of = [&](int i) { return (my_round(i) % PR) * 64 + lane; };   // chunk index inside the K or V tile
+  // round i of this wavefront: chunk slot of this lane inside the K or V tile, and whether it carries data
+  auto slot_of = [&](int i) { const int r = my_round(i); return (r < PRK ? r : r - PRK) * 64 + lane; };
+  auto live = [&](int i) {
+    const int c = slot_of(i);
+    return my_round(i) < PRK ? c < KB * CH : (c < KB * VCH && c % VCH < CH);
+  };
   auto chunk_off = [&](int i, int t) -> long long {   // element offset of this lane's chunk, round i
-    const int c = chunk_of(i);
-    int key = t * KB + c / CH;
+    const bool is_k = my_round(i) < PRK;
+    const int c = slot_of(i), per = is_k ? CH : VCH;
+    int key = t * KB + c / per;
     key = key < sk ? key : sk - 1;
-    return key * (my_round(i) < PR ? p.k_ss : p.v_ss) + 8 * (c % CH);
+    return key * (is_k ? p.k_ss : p.v_ss) + 8 * (c % per);
   };
   unsigned voff[MYR];   // byte offsets relative to the tile's first K / V row (full tiles)
 #pragma unroll
@@ -106,10 +116,10 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
 #pragma unroll
     for (int i = 0; i < MYR; ++i) {
       const int round = my_round(i);
-      const bool is_k = round < PR;
+      const bool is_k = round < PRK;
       const long long t_off = (long long)t * KB * (is_k ? p.k_ss : p.v_ss);
-      const int lds_elem = stage * STAGE_ELEMS + (is_k ? 0 : TILE_ELEMS) + 512 * (round % PR);
-      if (chunk_of(i) < NTC) {   // the last round of a tile is partial: lanes past the tile stay idle
+      const int lds_elem = stage * STAGE_ELEMS + (is_k ? 512 * round : TILE_ELEMS + 512 * (round - PRK));
+      if (live(i)) {   // idle lanes: past the tile, or on a constant chunk that must survive
         if (DIRECT) {
           const unsigned off = tail ? (unsigned)(2 * (chunk_off(i, t) - t_off)) : voff[i];
           dma16_to_lds((is_k ? kb_ : vb) + t_off, off, smem_addr + 2 * lds_elem);
@@ -130,6 +140,11 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
 
   // ---- prologue: first NST-1 tiles on their way, then the q fragments ----
   if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + NST * STAGE_ELEMS)[tid] = 0u;   // the slack is defined
+  for (int idx = tid; idx < NST * KB; idx += 256) {   // constant chunk of every V row of every stage
+    bf16x8 one = zero8();
+    one[0] = (bf16_t)1.0f;
+    *reinterpret_cast<bf16x8 *>(smem + (idx / KB) * STAGE_ELEMS + TILE_ELEMS + (idx % KB) * VP + D) = one;
+  }
   const int npre = ntile < NST - 1 ? ntile : NST - 1;
   for (int t = 0; t < npre; ++t) issue(t, t);
 
@@ -165,9 +180,8 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
   // per-lane fragment offsets inside a tile of 32 keys
   const int k_off = sigma(j) * RP + 8 * g;                                           // + 16 s
   const int i16 = lane & 15, q4 = lane >> 4;
-  const int v_off = (8 * (q4 >> 1) + (i16 >> 2)) * RP + 16 * (q4 & 1) + 4 * (i16 & 3);   // + (16 m + 4 hh) * RP + 32 dt
+  const int v_off = (8 * (q4 >> 1) + (i16 >> 2)) * VP + 16 * (q4 & 1) + 4 * (i16 & 3);   // + (16 m + 4 hh) * VP + 32 dt
   constexpr int LDT = D / 32, LLOC = D % 32;   // output tile / row that holds the softmax denominator
-  const bool ones_lane = j == LLOC;
 
   // S^T = K Q^T for one 32-key tile
   auto qk = [&](f32x16(&S)[NQT], const bf16_t *ktile) {
@@ -237,12 +251,11 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
     for (int m = 0; m < 2; ++m)
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        const bf16_t *vp = vtile + v_off + 16 * m * RP + 32 * dt;
-        const bf16x4 lo = lds_read_tr4(vp), hi = lds_read_tr4(vp + 4 * RP);
+        const bf16_t *vp = vtile + v_off + 16 * m * VP + 32 * dt;
+        const bf16x4 lo = lds_read_tr4(vp), hi = lds_read_tr4(vp + 4 * VP);
         bf16x8 vf;
         vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
         vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-        if (dt == LDT) vf = ones_lane ? splat8(1.0f) : vf;   // row D of V^T := 1 (rows past D: don't care)
 #pragma unroll
         for (int n = 0; n < NQT; ++n) oacc[n][dt] = mfma32(vf, pf[n][m], oacc[n][dt]);
       }
