@@ -26,8 +26,9 @@ struct TemporalParams {
   float c;            // log2(e) / sqrt(D)
 };
 
-// TP: 16 or 32, the power-of-two tile edge that holds T.
-template <typename T_, int D, int TP>
+// TP: 16 or 32, the power-of-two tile edge that holds T.  RT: rows of LDS staging per tensor
+// (T <= RT <= TP); fewer rows let more workgroups share a CU.
+template <typename T_, int D, int TP, int RT>
 __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams p) {
   using HD = HeadDim<D>;
   constexpr int DK = HD::DK, KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH, DKP = HD::DKP;
@@ -35,10 +36,10 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
   constexpr int NR = TP / 2;              // live accumulator registers (keys 16..31 unused when TP == 16)
   constexpr int NM = TP / 16;             // 16-key steps of the second product
   constexpr int OP = D + 8;               // pitch of the output staging rows (elements of T_)
-  constexpr int QK_BYTES = 2 * TP * DKP * 2;
-  constexpr int O_BYTES = TP * OP * (int)sizeof(T_);
+  constexpr int QK_BYTES = 2 * RT * DKP * 2;
+  constexpr int O_BYTES = RT * OP * (int)sizeof(T_);
   constexpr int A_BYTES = QK_BYTES > O_BYTES ? QK_BYTES : O_BYTES;   // q/k staging, reused for o
-  constexpr int V_BYTES = TP * DKP * 2;
+  constexpr int V_BYTES = RT * DKP * 2;
   constexpr int WAVE_BYTES = A_BYTES + V_BYTES;
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * WAVE_BYTES];
@@ -46,16 +47,16 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 31, g = lane >> 5;
   unsigned char *base = smem + wave * WAVE_BYTES;
-  bf16_t *Qs = reinterpret_cast<bf16_t *>(base);                   // [TP][DKP]
-  bf16_t *Ks = Qs + TP * DKP;                                      // [TP][DKP]
-  T_ *Os = reinterpret_cast<T_ *>(base);                           // [TP][OP], aliases Qs/Ks
-  bf16_t *Vs = reinterpret_cast<bf16_t *>(base + A_BYTES);         // [TP][DKP], rows >= T stay zero
+  bf16_t *Qs = reinterpret_cast<bf16_t *>(base);                   // [RT][DKP]
+  bf16_t *Ks = Qs + RT * DKP;                                      // [RT][DKP]
+  T_ *Os = reinterpret_cast<T_ *>(base);                           // [RT][OP], aliases Qs/Ks
+  bf16_t *Vs = reinterpret_cast<bf16_t *>(base + A_BYTES);         // [RT][DKP], rows >= T stay zero
 
   const int T = p.T;
   const float c = p.c;
 
   // value rows of frames that do not exist must be finite: zero the tile once
-  for (int idx = lane; idx < TP * DKP / 8; idx += 64) reinterpret_cast<bf16x8 *>(Vs)[idx] = zero8();
+  for (int idx = lane; idx < RT * DKP / 8; idx += 64) reinterpret_cast<bf16x8 *>(Vs)[idx] = zero8();
 
   const int waves_total = gridDim.x * 4;
   for (int prob = blockIdx.x * 4 + wave; prob < p.n_prob; prob += waves_total) {
@@ -67,7 +68,7 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
 
     // ---- global -> registers -> LDS, whole rows per instruction; the padding chunk of q and k
     //      rows is written as zeros.  All loads are issued before the first LDS store. ----
-    constexpr int NLD = (TP * CHZ + 63) / 64;
+    constexpr int NLD = (RT * CHZ + 63) / 64;
     bf16x8 q8[NLD], k8[NLD], v8[NLD];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
@@ -95,7 +96,8 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.0f;
-    const int krow = sigma(j) & (TP - 1), qrow = j & (TP - 1);
+    // rows past the staging area alias a staged row: such keys are masked, such queries never stored
+    const int krow = min(sigma(j) & (TP - 1), RT - 1), qrow = min(j & (TP - 1), RT - 1);
 #pragma unroll
     for (int st = 0; st < KSTEPS; ++st) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&Ks[krow * DKP + 16 * st + 8 * g]);
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
         bf16x8 vf;
         if (d < D) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) vf[e] = Vs[(16 * m + 8 * g + e) * DKP + d];
+          for (int e = 0; e < 8; ++e) vf[e] = Vs[min(16 * m + 8 * g + e, RT - 1) * DKP + d];   // keys >= T weigh 0
         } else {
           vf = (d == D) ? splat8(1.0f) : zero8();   // row D of V^T: all ones -> softmax denominator
         }
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
     constexpr int LR = 4 * (LLOC / 8) + (LLOC % 4), LG = (LLOC / 4) & 1;
     const float inv = 1.0f / __shfl(o[LDT][LR], j + 32 * LG);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // Qs / Ks are dead from here on
-    if (j < TP) {
+    if (j < RT) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll

@@ -78,9 +78,11 @@ int launch_temporal(int T_, int S, int H, const void *q, const void *k, const vo
   long long grid = (n_prob + 3) / 4;
   if (grid > 8192) grid = 8192;   // wavefronts loop over problems beyond this
   if (T_ <= 16)
-    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 16>), dim3((unsigned)grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 16, 16>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  else if (T_ <= 24)   // 24 staged rows: three workgroups per CU instead of two
+    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 32, 24>), dim3((unsigned)grid), dim3(256), 0, st, p);
   else
-    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 32>), dim3((unsigned)grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 32, 32>), dim3((unsigned)grid), dim3(256), 0, st, p);
   return PAB_OK;
 }
 

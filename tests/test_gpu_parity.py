@@ -52,6 +52,8 @@ SHAPES = [
     (W.TEMPORAL, 1, 9, 0, 2, 72, "bf16"),      # one frame: identity on V
     (W.TEMPORAL, 4, 64, 0, 4, 32, "f32"),      # Tiny
     (W.TEMPORAL, 32, 11, 0, 2, 72, "bf16"),    # full 32x32 tile
+    (W.TEMPORAL, 24, 13, 0, 2, 72, "bf16"),    # last clip length of the 24-row staging variant
+    (W.TEMPORAL, 25, 13, 0, 2, 72, "f32"),     # first of the 32-row variant
     (W.TEMPORAL, 33, 7, 0, 2, 72, "bf16"),     # beyond the wavefront-resident kernel: tiled fallback
     (W.TEMPORAL, 5, 300, 0, 16, 72, "f32"),
     (W.TEMPORAL, 16, 33, 0, 2, 32, "bf16"),
