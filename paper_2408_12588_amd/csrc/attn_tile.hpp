@@ -2,7 +2,7 @@
 // paper Sec. 2.1): o = softmax(q k^T / sqrt(D)) v per (batch, head), computed
 // with an online softmax over tiles of keys so that scores never reach memory.
 //
-// Work split: one workgroup = 4 wavefronts = 128*NQT consecutive queries of one
+// Work split: one workgroup = NWV wavefronts = 32*NQT*NWV consecutive queries of one
 // (batch, head); each wavefront owns NQT tiles of 32 queries whose q fragments
 // stay in registers.  Keys and values stream through a ring of NST LDS stages,
 // one 32-key tile per stage, stored row-major exactly as in memory (for bf16
@@ -43,12 +43,12 @@ struct TileParams {
   int n_qblk;     // query blocks per (batch, head)
 };
 
-template <typename T, int D, int NQT, int NST, int MINW, bool PIPE, bool DIRECT>
-__global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p) {
+template <typename T, int D, int NQT, int NWV, int NST, int MINW, bool PIPE, bool DIRECT>
+__global__ __launch_bounds__(64 * NWV, MINW) void attn_tile_kernel(const TileParams p) {
   using HD = HeadDim<D>;
   constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
   constexpr int KB = 32;             // keys per LDS stage = one MFMA tile
-  constexpr int QBLK = 128 * NQT;    // queries per workgroup
+  constexpr int QBLK = 32 * NQT * NWV;   // queries per workgroup
   constexpr int RP = D;              // row pitch of the K tile in LDS: rows packed as in memory
   constexpr int VCH = CH + 1;        // chunks per V row in LDS: CH of data, then the constant chunk {1, 0, ..}
   constexpr int VP = 8 * VCH;        // row pitch of the V tile
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
   constexpr int PRK = (KB * CH + 63) / 64;   // staging rounds (64 chunk slots each, the last maybe partial) of the K tile
   constexpr int PRV = (KB * VCH + 63) / 64;  // ... of the V tile (the slots of the constant chunks stay idle)
   constexpr int ROUNDS = PRK + PRV;          // K rounds, then V rounds
-  constexpr int MYR = (ROUNDS + 3) / 4;      // rounds per wavefront (the last may repeat a round)
+  constexpr int MYR = (ROUNDS + NWV - 1) / NWV;   // rounds per wavefront (the last may repeat a round)
   static_assert(!DIRECT || sizeof(T) == 2, "direct-to-LDS staging needs bf16 inputs");
   static_assert(NST >= 3 && NST <= 5 && (NST - 2) * MYR < 16, "ring depth / vmcnt immediates");
 
@@ -87,13 +87,13 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
   const int q_wave0 = qblk * QBLK + wave * (32 * NQT);
   const bool wave_active = q_wave0 < sq;
 
-  // ---- staging of key tile t into LDS stage `stage`.  The ROUNDS rounds are dealt to the 4
+  // ---- staging of key tile t into LDS stage `stage`.  The ROUNDS rounds are dealt to the
   //      wavefronts round-robin.  Rows past the end of the sequence re-read the last valid row:
   //      their scores are masked, so they carry no weight. ----
   const int ntile = (sk + 31) >> 5;          // 32-key tiles, the last possibly partial
   const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
 
-  auto my_round = [&](int i) { const int r = wave + 4 * i; return r < ROUNDS ? r : ROUNDS - 1; };
+  auto my_round = [&](int i) { const int r = wave + NWV * i; return r < ROUNDS ? r : ROUNDS - 1; };
   // round i of this wavefront: chunk slot of this lane inside the K or V tile, and whether it carries data
   auto slot_of = [&](int i) { const int r = my_round(i); return (r < PRK ? r : r - PRK) * 64 + lane; };
   auto live = [&](int i) {
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256, MINW) void attn_tile_kernel(const TileParams p
 
   // ---- prologue: first NST-1 tiles on their way, then the q fragments ----
   if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + NST * STAGE_ELEMS)[tid] = 0u;   // the slack is defined
-  for (int idx = tid; idx < NST * KB; idx += 256) {   // constant chunk of every V row of every stage
+  for (int idx = tid; idx < NST * KB; idx += 64 * NWV) {   // constant chunk of every V row of every stage
     bf16x8 one = zero8();
     one[0] = (bf16_t)1.0f;
     *reinterpret_cast<bf16x8 *>(smem + (idx / KB) * STAGE_ELEMS + TILE_ELEMS + (idx % KB) * VP + D) = one;
