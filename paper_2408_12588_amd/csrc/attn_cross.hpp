@@ -1,28 +1,38 @@
 // Cross attention (paper Sec. 2.1): every video token attends to the L text
 // tokens of the conditioning input.  L is short (<= 128 here), so per head the
-// keys and values fit in LDS once and for all, the softmax needs a single pass,
-// and the operation is bound by streaming q in and o out of HBM.
+// keys and values fit in LDS once and for all and the softmax needs a single
+// pass; what is left per token is streaming q in and o out of HBM, and a fixed
+// amount of matrix-core and exp work per 32-token tile.
 //
 // One workgroup = NW wavefronts serves one head: it stages that head's K and V
 // rows ([L, D], row-major as in memory) into LDS once, then each wavefront walks
 // over 32-query tiles of the head with a stride of all wavefronts serving it.
 // The wavefronts never synchronise with each other after the K/V load.
 //
-// Per tile a wavefront
-//   - has the tile's 32 q rows copied global -> LDS by direct loads that were
-//     issued two tiles ahead (three per-wavefront buffers), 16 bytes per lane
-//     with consecutive lanes on consecutive chunks of a row.  Two tiles, not
-//     one: loads and stores share one in-order-per-kind counter, and with two
-//     tiles of loads behind it a tile can be waited for without also waiting
-//     for the stores of the tile before it;
-//   - computes S^T = K Q^T for all keys (bf16 MFMA, keys x queries, so the
-//     softmax statistics are per-lane scalars), one max, P^T = exp2(c(S^T - m))
-//     in registers, O^T = V^T P^T with V^T read transposed from LDS; V rows in
-//     LDS carry an extra chunk {1, 0, ..}, so row D of O^T is the softmax
-//     denominator, accumulated on the matrix core;
-//   - writes the normalised tile into the LDS buffer its q rows came from and
-//     from there to global memory, again whole rows per instruction.
+// A wavefront owns two LDS tile buffers: X receives q tiles (direct global ->
+// LDS loads, 16 bytes per lane, consecutive lanes on consecutive chunks of a
+// row), Y holds the finished output tile until it is written out, whole rows
+// per instruction.  The loop over tiles is software pipelined so that the
+// matrix core always has work while the softmax runs on the vector ALU:
+//
+//   iteration for tile t (its scores S^T = K Q^T are already in registers):
+//     wait for all outstanding memory operations (all one iteration old)
+//     write tile t-1 from Y to global memory
+//     fetch the q operands of tile t+1 from X, then request tile t+2 into X
+//     row max of S; for each 32-key tile kt:
+//         P^T = exp2(c (S^T - max))            (vector ALU)
+//         O^T += V^T P^T                       (matrix core)
+//         S^T[kt] of tile t+1 = K[kt] Q^T      (matrix core, reuses the registers)
+//     normalise O and stage it in Y
+//
+// Keys are permuted so that the accumulator registers of the first product are
+// the B operand of the second.  V rows in LDS carry an extra chunk {1, 0, ..}:
+// row D of O^T is then the softmax denominator.  K rows past L repeat row L-1
+// (so the row max is unchanged) while V rows past L are all zero, constant
+// chunk included: such keys add nothing to numerator or denominator and no
+// score has to be masked.
 #pragma once
+#include <type_traits>
 #include "mfma_util.hpp"
 
 namespace pab {
@@ -35,27 +45,27 @@ struct CrossParams {
   float c;             // log2(e) / sqrt(D)
 };
 
-// LT: 32-key tiles that hold L (1..4).  NW: wavefronts per workgroup.  NB: q/o tile buffers per
-// wavefront (2 or 3); q tiles are requested NB-1 tiles ahead.
-template <int D, int LT, int NW, int NB>
+// LT: 32-key tiles that hold L (1..4).  NW: wavefronts per workgroup.
+template <int D, int LT, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p) {
   using HD = HeadDim<D>;
   using T = bf16_t;
   constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
-  constexpr int LP = 32 * LT;               // key rows held in LDS (rows past L repeat row L-1, masked)
+  constexpr int LP = 32 * LT;               // key rows held in LDS
   constexpr int RP = D;                     // row pitch: rows packed as in memory
-  constexpr int VCH = CH + 1, VP = 8 * VCH; // V rows in LDS: CH data chunks, then the constant chunk {1, 0, ..}
+  constexpr int VCH = CH + 1, VP = 8 * VCH; // V rows in LDS: CH data chunks, then the constant chunk
   constexpr int K_ELEMS = LP * RP, V_ELEMS = LP * VP, KV_ELEMS = K_ELEMS + V_ELEMS;
-  constexpr int QB_ELEMS = 32 * RP;         // one q / o tile buffer
+  constexpr int QB_ELEMS = 32 * RP;         // one tile buffer
+  constexpr int NCHUNK = 32 * CH;           // 16-byte chunks of a tile
   constexpr int KR = (LP * CH + 63) / 64;   // staging rounds (64 chunk slots) for K
-  constexpr int VR = (LP * VCH + 63) / 64;  // ... for V (the slots of the constant chunks stay idle)
-  constexpr int QR = (32 * CH + 63) / 64;   // staging rounds for a q tile (the last may be partial)
-  constexpr int SLACK = 64;
+  constexpr int VR = (LP * VCH + 63) / 64;  // ... for V
+  constexpr int QR = (NCHUNK + 63) / 64;    // rounds for a q / o tile (the last may be partial)
+  constexpr int ZERO_ELEMS = 64;            // zeros behind the buffers (operand columns past D)
   static_assert(LT >= 1 && LT <= 4, "keys must fit four 32-key tiles");
-  static_assert((NB == 2 || NB == 3) && 2 * QR < 16, "buffers / vmcnt immediate");
 
-  __shared__ __attribute__((aligned(16))) bf16_t smem[KV_ELEMS + NW * NB * QB_ELEMS + SLACK];
+  __shared__ __attribute__((aligned(16))) bf16_t smem[KV_ELEMS + NW * 2 * QB_ELEMS + ZERO_ELEMS];
   bf16_t *Ks = smem, *Vs = smem + K_ELEMS;
+  bf16_t *zeros = smem + KV_ELEMS + NW * 2 * QB_ELEMS;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -90,49 +100,79 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
   T *oh = reinterpret_cast<T *>(p.o) + (long long)head * D;
   const int n_tok = p.n_tok, L = p.L;
   const int stride = parts * NW;
-  bf16_t *qbuf = smem + KV_ELEMS + wave * (NB * QB_ELEMS);
+  bf16_t *X = smem + KV_ELEMS + wave * (2 * QB_ELEMS), *Y = X + QB_ELEMS;
+  const unsigned x_addr = smem_addr + 2 * (unsigned)(X - smem);
 
-  // ---- K and V of the head, rounds dealt round-robin to the wavefronts ----
+  // ---- K and V of the head, rounds dealt round-robin to the wavefronts.  Slots that no load
+  //      fills (V rows past L, the constant chunks) are written as ordinary LDS stores. ----
   for (int r = wave; r < KR + VR; r += NW) {
-    const bool is_k = r < KR;
-    const int c = (is_k ? r : r - KR) * 64 + lane, per = is_k ? CH : VCH;
-    if (c < LP * per && c % per < CH) {
-      int key = c / per;
-      key = key < L ? key : L - 1;
-      dma16_to_lds(is_k ? kh : vh, (unsigned)(2 * (key * row + 8 * (c % per))),
-                   smem_addr + 2 * (is_k ? 512 * r : K_ELEMS + 512 * (r - KR)));
+    if (r < KR) {
+      const int c = r * 64 + lane;
+      if (c < LP * CH) {
+        int key = c / CH;
+        key = key < L ? key : L - 1;
+        dma16_to_lds(kh, (unsigned)(2 * (key * row + 8 * (c % CH))), smem_addr + 1024 * r);
+      }
+    } else {
+      const int c = (r - KR) * 64 + lane, key = c / VCH, chunk = c % VCH;
+      const bool real = c < LP * VCH && key < L && chunk < CH;
+      if (real) dma16_to_lds(vh, (unsigned)(2 * (key * row + 8 * chunk)), smem_addr + 2 * K_ELEMS + 1024 * (r - KR));
+      if (c < LP * VCH && !real) {
+        bf16x8 fill = zero8();
+        if (chunk == CH && key < L) fill[0] = (bf16_t)1.0f;
+        *reinterpret_cast<bf16x8 *>(Vs + 8 * c) = fill;
+      }
     }
   }
-  for (int idx = tid; idx < LP; idx += 64 * NW) {   // constant chunk of every V row
-    bf16x8 one = zero8();
-    one[0] = (bf16_t)1.0f;
-    *reinterpret_cast<bf16x8 *>(Vs + idx * VP + D) = one;
-  }
-  if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + KV_ELEMS + NB * NW * QB_ELEMS)[tid] = 0u;
+  if (tid < ZERO_ELEMS / 2) reinterpret_cast<unsigned *>(zeros)[tid] = 0u;
 
-  // ---- q tile t -> this wavefront's buffer `b`: QR direct loads, rows past the end repeat the last.
-  //      Token offsets can exceed 32 bits: the base moves with the tile, the lane offset stays small. ----
-  auto stage_q = [&](int t, int b) {
+  // ---- lane constants of the tile copies: chunk c = 64 r + lane of a tile is row c / CH, chunk
+  //      c % CH of that row; in LDS the tile is packed, so the chunk sits at element 8 c. ----
+  int trow[QR];
+  unsigned voff[QR];   // byte offset of the chunk from the tile's first row in global memory
+#pragma unroll
+  for (int r = 0; r < QR; ++r) {
+    const int c = r * 64 + lane;
+    trow[r] = c / CH;
+    voff[r] = (unsigned)(2 * (trow[r] * row + 8 * (c % CH)));
+  }
+
+  // q tile t -> X.  Rows past the last token repeat the last one (their results are never stored).
+  // Token offsets can exceed 32 bits: the base moves with the tile, the lane offset stays small.
+  auto stage_q = [&](int t) {
     const int tok0 = 32 * t;
     const T *base = qh + (long long)tok0 * row;
+    const bool whole = tok0 + 32 <= n_tok;
 #pragma unroll
     for (int r = 0; r < QR; ++r) {
       const int c = r * 64 + lane;
-      if (c < 32 * CH) {
-        int tr = c / CH;
-        tr = tok0 + tr < n_tok ? tr : n_tok - 1 - tok0;
-        dma16_to_lds(base, (unsigned)(2 * (tr * row + 8 * (c % CH))), smem_addr + 2 * (int)(qbuf - smem) + 2 * b * QB_ELEMS + 1024 * r);
+      if (c < NCHUNK) {
+        unsigned off = voff[r];
+        if (!whole) {
+          const int tr = min(trow[r], n_tok - 1 - tok0);
+          off = (unsigned)(2 * (tr * row + 8 * (c - CH * trow[r])));
+        }
+        dma16_to_lds(base, off, x_addr + 1024 * r);
       }
     }
   };
 
-  constexpr int PD = NB - 1;   // prefetch distance in tiles
-  int t = t_lo + part * NW + wave;
+  // finished tile t: Y -> global memory, whole rows per instruction
+  auto store_tile = [&](int t) {
+    char *ot = reinterpret_cast<char *>(oh + (long long)(32 * t) * row);
+    bf16x8 val[QR];
 #pragma unroll
-  for (int d = 0; d < PD; ++d)
-    if (t + d * stride < t_hi) stage_q(t + d * stride, d);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // K, V (this wavefront's share) and the first q tiles have landed
+    for (int r = 0; r < QR; ++r) val[r] = *reinterpret_cast<const bf16x8 *>(Y + 8 * min(r * 64 + lane, NCHUNK - 1));
+#pragma unroll
+    for (int r = 0; r < QR; ++r)
+      if (r * 64 + lane < NCHUNK && 32 * t + trow[r] < n_tok) *reinterpret_cast<bf16x8 *>(ot + voff[r]) = val[r];
+  };
+
+  int t = t_lo + part * NW + wave;
+  if (t < t_hi) stage_q(t);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // K, V (this wavefront's share) and the first q tile have landed
   __syncthreads();                      // ... everyone's share of K and V
+  if (t >= t_hi) return;
 
   const float c = p.c;
   const int k_off = sigma(j) * RP + 8 * g;                                             // + 32 kt * RP + 16 s
@@ -140,50 +180,31 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
   const int v_off = (8 * (q4 >> 1) + (i16 >> 2)) * VP + 16 * (q4 & 1) + 4 * (i16 & 3);   // + (32 kt + 16 m + 4 hh) * VP + 32 dt
   constexpr int LDT = D / 32, LLOC = D % 32;
   constexpr int LR = 4 * (LLOC / 8) + (LLOC % 4), LG = (LLOC / 4) & 1;
+  // q operand (B): query j, columns 16 s + 8 g; a chunk past D is read from the zeros
+  const bf16_t *q_src = X + j * RP + 8 * g;
+  const bf16_t *q_last = (16 * (KSTEPS - 1) + 8 * g < D) ? q_src + 16 * (KSTEPS - 1) : zeros;
 
-  int cur = 0;   // ring position of tile t's buffer
-  for (; t < t_hi; t += stride, cur = cur == NB - 1 ? 0 : cur + 1) {
-    bf16_t *qb = qbuf + cur * QB_ELEMS;
-    // Request the tile PD tiles ahead into the buffer the previous tile was written out from, then
-    // wait for tile t.  Loads complete in order among themselves (so do stores, but not against
-    // loads): tile t's loads are followed by those of the `later` tiles already requested, so once at
-    // most later*QR operations are in flight tile t has landed, whatever earlier stores are doing.
-    if (t + PD * stride < t_hi) stage_q(t + PD * stride, cur == 0 ? NB - 1 : cur - 1);
-    const int left = (t_hi - 1 - t) / stride;
-    const int later = left < PD ? left : PD;
-    if (later >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * QR));
-    else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | QR);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // ---- q fragments (B operand): query j, columns 16 s + 8 g; columns past D are zero ----
-    bf16x8 qf[KSTEPS];
+  bf16x8 qn[KSTEPS];   // q operands of the tile whose scores are computed next
+  auto fetch_q = [&]() {
+#pragma unroll
+    for (int s = 0; s < KSTEPS - 1; ++s) qn[s] = *reinterpret_cast<const bf16x8 *>(q_src + 16 * s);
+    qn[KSTEPS - 1] = *reinterpret_cast<const bf16x8 *>(q_last);
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // the reads of X are done before a later load may overwrite it
+  };
+  f32x16 S[LT];
+  auto scores = [&](int kt) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) S[kt][r] = 0.0f;
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
-      qf[s] = *reinterpret_cast<const bf16x8 *>(qb + j * RP + 16 * s + 8 * g);
-      if (16 * s + 8 >= D) qf[s] = (16 * s + 8 * g < D) ? qf[s] : zero8();
+      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(Ks + k_off + 32 * kt * RP + 16 * s);
+      S[kt] = mfma32(kf, qn[s], S[kt]);
     }
+  };
 
-    // ---- S^T = K Q^T over all keys ----
-    f32x16 S[LT];
-#pragma unroll
-    for (int kt = 0; kt < LT; ++kt) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) S[kt][r] = 0.0f;
-#pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(Ks + k_off + 32 * kt * RP + 16 * s);
-        S[kt] = mfma32(kf, qf[s], S[kt]);
-      }
-    }
-    // keys past L take no probability mass (only the last tile can hold any)
-    if ((L & 31) != 0) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (32 * (LT - 1) + key_of_reg(r, g) >= L) S[LT - 1][r] = -INFINITY;
-    }
-
-    // ---- single-pass softmax of lane j's query ----
+  // softmax and second product of the tile in S; with MORE, the scores of the next tile replace S
+  auto tile_body = [&](auto more_tag) {
+    constexpr bool MORE = decltype(more_tag)::value;
     float mx = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < LT; ++kt) {
@@ -197,10 +218,9 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
       a = fmaxf(fmaxf(a, S[kt][14]), S[kt][15]);
       mx = fmaxf(mx, fmaxf(a, b2));
     }
-    mx = max_pair(mx);   // key 0 is always valid, so mx is finite
+    mx = max_pair(mx);
     const float mc = mx * c;
 
-    // ---- O^T = V^T P^T, tile by tile of keys ----
     f32x16 oacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -223,30 +243,50 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
           vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
           oacc[dt] = mfma32(vf, pf[m], oacc[dt]);
         }
+      if (MORE) scores(kt);
     }
 
-    // ---- normalise, stage the tile [token][d] in the buffer its q rows came from, write whole rows ----
+    // normalise and stage the tile [token][d] in Y
     const float inv = 1.0f / __shfl(oacc[LDT][LR], j + 32 * LG);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // all q fragment reads are done
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
         const int d0 = 32 * dt + 8 * rq + 4 * g;
         if (d0 < D)
-          Io<T>::store4(qb + j * RP + d0, oacc[dt][4 * rq] * inv, oacc[dt][4 * rq + 1] * inv,
+          Io<T>::store4(Y + j * RP + d0, oacc[dt][4 * rq] * inv, oacc[dt][4 * rq + 1] * inv,
                         oacc[dt][4 * rq + 2] * inv, oacc[dt][4 * rq + 3] * inv);
       }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    T *ot = oh + (long long)(32 * t) * row;
+  };
+
+  // ---- prologue: scores of the first tile, second tile requested ----
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  fetch_q();
+  if (t + stride < t_hi) stage_q(t + stride);
 #pragma unroll
-    for (int r = 0; r < QR; ++r) {
-      const int cidx = r * 64 + lane;
-      const int tr = cidx / CH, cc = cidx % CH;
-      if (cidx < 32 * CH && 32 * t + tr < n_tok)
-        *reinterpret_cast<bf16x8 *>(ot + tr * row + 8 * cc) = *reinterpret_cast<const bf16x8 *>(qb + tr * RP + 8 * cc);
+  for (int kt = 0; kt < LT; ++kt) scores(kt);
+
+  int t_prev = -1;
+  for (;;) {
+    const bool more = t + stride < t_hi;
+    // Everything still in flight (the q tile for the next iteration, the stores of the tile before
+    // the previous one) was issued an iteration ago.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    if (t_prev >= 0) store_tile(t_prev);
+    if (more) {
+      fetch_q();
+      if (t + 2 * stride < t_hi) stage_q(t + 2 * stride);
+      tile_body(std::true_type{});
+    } else {
+      tile_body(std::false_type{});
     }
+    t_prev = t;
+    t += stride;
+    if (!more) break;
   }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  store_tile(t_prev);
 }
 
 }  // namespace pab

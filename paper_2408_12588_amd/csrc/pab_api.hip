@@ -89,7 +89,6 @@ int launch_temporal(int T_, int S, int H, const void *q, const void *k, const vo
 
 // Cross attention with few keys and bf16 rows: K and V stay in LDS, q and o stream.
 constexpr int CROSS_NW = 4;    // wavefronts per workgroup
-constexpr int CROSS_NB = 2;    // q/o tile buffers per wavefront (two workgroups fit a CU's LDS)
 
 template <int D>
 int launch_cross(int n_tok, int L, int H, const void *q, const void *k, const void *v, void *o, hipStream_t st) {
@@ -106,10 +105,10 @@ int launch_cross(int n_tok, int L, int H, const void *q, const void *k, const vo
   p.wg_per_head = per_head;
   const dim3 grid((unsigned)(H * per_head)), block(64 * CROSS_NW);
   switch ((L + 31) / 32) {
-    case 1: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 1, CROSS_NW, CROSS_NB>), grid, block, 0, st, p); break;
-    case 2: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 2, CROSS_NW, CROSS_NB>), grid, block, 0, st, p); break;
-    case 3: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 3, CROSS_NW, CROSS_NB>), grid, block, 0, st, p); break;
-    default: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 4, CROSS_NW, CROSS_NB>), grid, block, 0, st, p); break;
+    case 1: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 1, CROSS_NW>), grid, block, 0, st, p); break;
+    case 2: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 2, CROSS_NW>), grid, block, 0, st, p); break;
+    case 3: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 3, CROSS_NW>), grid, block, 0, st, p); break;
+    default: hipLaunchKernelGGL((pab::attn_cross_kernel<D, 4, CROSS_NW>), grid, block, 0, st, p); break;
   }
   return PAB_OK;
 }
