@@ -12,6 +12,7 @@
 
 #include "../../include/pab.h"
 #include "attn_cross.hpp"
+#include "attn_cross_long.hpp"
 #include "attn_temporal.hpp"
 #include "attn_tile.hpp"
 
@@ -113,6 +114,32 @@ int launch_cross(int n_tok, int L, int H, const void *q, const void *k, const vo
   return PAB_OK;
 }
 
+// Cross attention with up to 512 keys and bf16 rows: K and V of a head still fit in LDS, the
+// online softmax runs over its key tiles.  One workgroup per CU.
+constexpr int CROSSL_NW = 16;   // wavefronts per workgroup
+constexpr int CROSSL_MINW = 4;  // ... per SIMD
+constexpr int CROSSL_MAX_L = 512;
+
+template <int D>
+int launch_cross_long(int n_tok, int L, int H, const void *q, const void *k, const void *v, void *o, hipStream_t st) {
+  pab::CrossLongParams p;
+  p.q = q; p.k = k; p.v = v; p.o = o;
+  p.n_tok = n_tok; p.L = L; p.n_head = H;
+  p.c = (float)(1.4426950408889634 / std::sqrt((double)D));
+  const int ntile = (n_tok + 31) / 32;
+  int per_head = (256 / H + 7) / 8 * 8;
+  if (ntile < per_head * CROSSL_NW) per_head = (ntile + CROSSL_NW - 1) / CROSSL_NW;
+  if (per_head < 1) per_head = 1;
+  p.wg_per_head = per_head;
+  const dim3 grid((unsigned)(H * per_head)), block(64 * CROSSL_NW);
+  const int lt = (L + 31) / 32;
+  if (lt <= 6) hipLaunchKernelGGL((pab::attn_cross_long_kernel<D, 6, CROSSL_NW, CROSSL_MINW>), grid, block, 0, st, p);
+  else if (lt <= 8) hipLaunchKernelGGL((pab::attn_cross_long_kernel<D, 8, CROSSL_NW, CROSSL_MINW>), grid, block, 0, st, p);
+  else if (lt <= 10) hipLaunchKernelGGL((pab::attn_cross_long_kernel<D, 10, CROSSL_NW, CROSSL_MINW>), grid, block, 0, st, p);
+  else hipLaunchKernelGGL((pab::attn_cross_long_kernel<D, 16, CROSSL_NW, CROSSL_MINW>), grid, block, 0, st, p);
+  return PAB_OK;
+}
+
 template <typename T, int D>
 int launch_kind(int kind, int T_, int S, int L, int H, const void *q, const void *k, const void *v, void *o,
                 hipStream_t st) {
@@ -126,6 +153,7 @@ int launch_kind(int kind, int T_, int S, int L, int H, const void *q, const void
       const long long tok = (long long)T_ * S;
       if (tok > 0x7fffffffLL) return fail(PAB_EINVAL, "too many tokens");
       if (sizeof(T) == 2 && L <= 128 && H <= 512) return launch_cross<D>((int)tok, L, H, q, k, v, o, st);
+      if (sizeof(T) == 2 && L <= CROSSL_MAX_L && H <= 512) return launch_cross_long<D>((int)tok, L, H, q, k, v, o, st);
       return launch_tile<T, D>(1, H, (int)tok, L, 0, row, 0, row, q, k, v, o, st);
     }
   }

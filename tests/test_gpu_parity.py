@@ -66,7 +66,16 @@ SHAPES = [
     (W.CROSS, 1, 31, 33, 16, 72, "bf16"),      # fewer tokens than one tile, one key past a tile edge
     (W.CROSS, 7, 333, 97, 8, 72, "bf16"),      # many tiles per wavefront, heads spread over the XCDs
     (W.CROSS, 3, 200, 60, 2, 32, "bf16"),
-    (W.CROSS, 2, 150, 129, 2, 72, "bf16"),     # one key too many for the LDS-resident kernel: tiled fallback
+    (W.CROSS, 2, 150, 129, 2, 72, "bf16"),     # one key too many for the single-pass kernel: online softmax, K/V in LDS
+    (W.CROSS, 17, 90, 300, 16, 72, "bf16"),    # config 4's text length: ten key tiles, the last ragged
+    (W.CROSS, 3, 77, 192, 3, 72, "bf16"),      # fills the 6-tile LDS variant exactly
+    (W.CROSS, 2, 100, 193, 2, 72, "bf16"),     # first length of the 8-tile variant
+    (W.CROSS, 2, 61, 257, 5, 32, "bf16"),      # 10-tile variant, head dim 32
+    (W.CROSS, 1, 45, 320, 2, 72, "bf16"),      # fills the 10-tile variant
+    (W.CROSS, 2, 150, 321, 2, 72, "bf16"),     # 16-tile variant, 11 tiles in use
+    (W.CROSS, 1, 40, 512, 2, 72, "bf16"),      # longest text the LDS-resident kernel takes
+    (W.CROSS, 1, 40, 513, 2, 72, "bf16"),      # beyond it: streaming tile kernel
+    (W.CROSS, 2, 64, 200, 2, 72, "f32"),       # fp32 rows: streaming tile kernel
 ]
 
 
@@ -88,7 +97,8 @@ def test_attention_matches_oracle(pab, kind, T, S, L, H, D, dtype):
 def test_peaked_queries_small(pab):
     # the stress configuration's value recipe (5% of query rows scaled by 8) at a size the
     # oracle can do in full: sharp and diffuse rows share tiles
-    for kind, (T, S, L) in ((W.SPATIAL, (2, 333, 0)), (W.TEMPORAL, (16, 41, 0)), (W.CROSS, (2, 200, 120))):
+    for kind, (T, S, L) in ((W.SPATIAL, (2, 333, 0)), (W.TEMPORAL, (16, 41, 0)), (W.CROSS, (2, 200, 120)),
+                            (W.CROSS, (2, 200, 300))):
         q, k, v = rand_qkv(kind, T, S, L, 4, 72, "bf16", seed=77, scale_rows=0.05)
         out = pab.pab_attention_compute(kind, q.to(DEV), k.to(DEV), v.to(DEV))
         torch.cuda.synchronize()
