@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--profile-kind", default=None, choices=["spatial", "temporal", "cross"],
                     help="counter-collection mode: one 1 GiB device copy (calibration), then --kind-reps launches "
                          "of this kind over the rotating pool; prints no result line")
+    ap.add_argument("--input-scale", type=float, default=1.0,
+                    help="profile mode only: multiply the inputs by this (0 = all-zero operands, the same "
+                         "instruction stream with no data toggling: shows how far the clock follows the data)")
     return ap.parse_args()
 
 
@@ -132,6 +135,10 @@ def main():
         b = torch.empty_like(a)
         b.copy_(a)                                  # reads 1 GiB, writes 1 GiB: scale for FETCH_SIZE / WRITE_SIZE
         out = torch.empty(full, device=dev, dtype=dt)
+        if args.input_scale != 1.0:
+            for ts in pool + (kv_cross or []):
+                for x in ts:
+                    x.mul_(args.input_scale)
         for i in range(args.kind_reps):
             pab.pab_attention_compute(kind, *inputs(i, kind), out=out)
         torch.cuda.synchronize()
