@@ -196,6 +196,11 @@ def main():
     # ---- schedule accounting ----
     skipped_flop_fraction = 1.0 - total_flops / sum(flops0) if sum(flops0) else 0.0
     time_reduction = 1.0 - sec / sec0
+    # what the per-kind kernel times predict (reuse is free, so a kind's time scales with its launches)
+    ms_of = [kinds.get(n, {}).get("ms_per_call", 0.0) for n in W.KIND_NAMES]
+    t_pab = sum(l * m for l, m in zip(launches, ms_of))
+    t_all = sum(l * m for l, m in zip(launches0, ms_of))
+    time_weighted_prediction = 1.0 - t_pab / t_all if t_all else 0.0
 
     result = {
         "metric": "attention TFLOP/s + %roofline; per-video attention latency PAB vs no-PAB",
@@ -212,6 +217,10 @@ def main():
         "roofline": roofline,
         "latency_ms": {"pab": round(sec * 1e3, 3), "no_pab": round(sec0 * 1e3, 3), "steps": K},
         "pab": {"time_reduction": round(time_reduction, 4), "skipped_flop_fraction": round(skipped_flop_fraction, 4),
+                "gap_abs": round(time_reduction - skipped_flop_fraction, 4),
+                "gap_rel": round((time_reduction - skipped_flop_fraction) / skipped_flop_fraction, 4) if skipped_flop_fraction else None,
+                "time_weighted_prediction": round(time_weighted_prediction, 4),
+                "skipped_launch_fraction": [round(1.0 - a / b, 4) if b else None for a, b in zip(launches, launches0)],
                 "launches_pab": launches, "launches_no_pab": launches0,
                 "effective_tflops": round(sum(flops0) / sec / 1e12, 3)},
         "kinds": kinds,
