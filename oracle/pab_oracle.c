@@ -75,6 +75,35 @@ long pab_oracle_source_step(long step, long lo, long hi, long n)
 }
 
 /*
+ * The paper gives broadcast windows as diffusion timesteps, written
+ * [t_start - t_end] on a scale where 1000 is the beginning of denoising and 0
+ * its end (App. A.2.1, table of attention broadcast configurations).  A
+ * sampler visits a list of timesteps, one per step, that never increases.
+ * Step s lies in the window iff t_end <= timesteps[s] <= t_start (both ends
+ * taken as inclusive: the paper does not say).  Marks every step, then
+ * reports how many are inside and the first and last of them.
+ * Returns the count (0: *lo and *hi untouched), or -1 on meaningless
+ * arguments (n_steps < 1, t_start < t_end, a timestep list that increases).
+ */
+long pab_oracle_window(const double *timesteps, long n_steps, double t_start,
+                       double t_end, long *lo, long *hi)
+{
+    long s, count = 0, first = -1, last = -1;
+    if (!timesteps || n_steps < 1 || t_start < t_end) return -1;
+    for (s = 1; s < n_steps; ++s)
+        if (timesteps[s] > timesteps[s - 1]) return -1;
+    for (s = 0; s < n_steps; ++s) {
+        int inside = timesteps[s] <= t_start && timesteps[s] >= t_end;
+        if (!inside) continue;
+        if (first < 0) first = s;
+        last = s;
+        ++count;
+    }
+    if (count > 0) { *lo = first; *hi = last; }
+    return count;
+}
+
+/*
  * softmax(Q K^T / sqrt(D)) V for n_batch x n_head independent problems.
  *
  * q, o: sq query rows; k, v: sk key rows; each row has d contiguous fp64

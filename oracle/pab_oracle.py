@@ -58,6 +58,9 @@ def _load():
         lib.pab_oracle_schedule.argtypes = [ctypes.c_long] * 4
         lib.pab_oracle_source_step.restype = ctypes.c_long
         lib.pab_oracle_source_step.argtypes = [ctypes.c_long] * 4
+        lib.pab_oracle_window.restype = ctypes.c_long
+        lib.pab_oracle_window.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_long, ctypes.c_double,
+                                          ctypes.c_double, ctypes.POINTER(ctypes.c_long), ctypes.POINTER(ctypes.c_long)]
         lib.pab_oracle_attention.restype = ctypes.c_int
         dp = ctypes.POINTER(ctypes.c_double)
         lp = ctypes.POINTER(ctypes.c_long)
@@ -89,6 +92,18 @@ def source_step(step: int, lo: int, hi: int, n: int) -> int:
 def schedule_row(n_steps: int, lo: int, hi: int, n: int) -> str:
     """One character per step: 'C' computed, 'R' reused."""
     return "".join("CR"[schedule(s, lo, hi, n)] for s in range(n_steps))
+
+
+def window_from_timesteps(timesteps, t_start: float, t_end: float):
+    """(lo, hi) step indices of the timestep window [t_start - t_end] (paper App. A.2.1:
+    1000 = start of denoising, 0 = end), or None if no step of the sampler falls inside."""
+    ts = np.ascontiguousarray(np.asarray(timesteps, dtype=np.float64))
+    lo, hi = ctypes.c_long(-1), ctypes.c_long(-1)
+    r = _load().pab_oracle_window(ts.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), len(ts),
+                                  float(t_start), float(t_end), ctypes.byref(lo), ctypes.byref(hi))
+    if r < 0:
+        raise ValueError("bad window arguments")
+    return None if r == 0 else (lo.value, hi.value)
 
 
 # --------------------------------------------------------------------------

@@ -40,3 +40,22 @@ def golden_attention():
             parts = line.split()
             out[parts[0]] = [float(x) for x in parts[1:]]
     return out
+
+
+@pytest.fixture(scope="session")
+def golden_timestep_windows():
+    """(windows, rows, presets) of tests/golden/timestep_windows.txt."""
+    windows, rows, presets = [], [], []
+    with open(golden_path("timestep_windows.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            p = line.split()
+            if p[0] == "row":
+                rows.append((p[1], int(p[2]), p[3]))
+            elif p[0] == "preset":
+                presets.append((p[1], int(p[2]), tuple(int(x) for x in p[3:6]), float(p[6]), float(p[7])))
+            else:
+                windows.append((p[0],) + tuple(int(x) for x in p[1:]))
+    return windows, rows, presets
