@@ -92,6 +92,33 @@ int pab_schedule(int kind, int step, int range_lo, int range_hi, int interval);
 int pab_source_step(int kind, int step, int range_lo, int range_hi, int interval);
 
 /*
+ * The paper states its broadcast windows as diffusion timesteps, e.g.
+ * [930-450] on a scale where 1000 is the beginning of denoising and 0 its end
+ * (App. A.2.1, table of attention broadcast configurations).  This maps such a
+ * window onto the steps of a sampler (host, pure): timesteps[s] is the
+ * timestep the sampler visits at step s, n_steps values that never increase.
+ * Step s is inside iff t_end <= timesteps[s] <= t_start (both ends inclusive).
+ * Returns the number of steps inside and, if that is >= 1, writes the first
+ * and last of them to *range_lo / *range_hi (the values pab_config and
+ * pab_schedule take).  0 means no step of this sampler falls in the window:
+ * nothing is to be broadcast (use interval 1); *range_lo / *range_hi are then
+ * left alone.  PAB_EINVAL: NULL pointer, n_steps < 1, t_start < t_end, or a
+ * timestep list that increases somewhere.
+ */
+int pab_window_from_timesteps(const double *timesteps, int n_steps, double t_start, double t_end,
+                              int *range_lo, int *range_hi);
+
+/*
+ * The settings the paper evaluates (App. A.2.1, same table): broadcast ranges
+ * for spatial / temporal / cross attention and the timestep window, per model
+ * and per level (0 = the best-quality setting PAB_246 / PAB_235, 1 and 2 the
+ * faster ones).  Writes interval[0..2], *t_start and *t_end.
+ * PAB_EINVAL: model not a pab_model, level outside 0..2, NULL pointer.
+ */
+enum pab_model { PAB_OPEN_SORA = 0, PAB_OPEN_SORA_PLAN = 1, PAB_LATTE = 2 };
+int pab_preset(int model, int level, int interval[3], double *t_start, double *t_end);
+
+/*
  * Bytes of device memory the broadcast cache of `cfg` needs: one output tensor
  * [T, S, H, D] per (block, present kind), each slot rounded up to 256 bytes.
  * Returns 0 if cfg is NULL or invalid (pab_last_error says why).

@@ -30,8 +30,12 @@
  *     only decides which axis of the activation tensor is "batch" and which
  *     is "sequence".
  *
- * parity unpinned: nothing the paper prints fixes the phase of the period or
- * the inclusiveness of the segment ends (readings above); every other function
+ *  3. The mapping of a broadcast window given in diffusion timesteps
+ *     (App. A.2.1) onto the step indices of a sampler's timestep list.
+ *
+ * parity unpinned: nothing the paper prints fixes the phase of the period,
+ * the inclusiveness of the segment ends, or the inclusiveness of a timestep
+ * window's ends (readings above and at pab_oracle_window); everything else
  * here is pinned by the CPU tests.
  */
 #include <math.h>

@@ -236,6 +236,42 @@ int pab_source_step(int kind, int step, int range_lo, int range_hi, int interval
   return step - (step - range_lo) % interval;
 }
 
+int pab_window_from_timesteps(const double *timesteps, int n_steps, double t_start, double t_end,
+                              int *range_lo, int *range_hi) {
+  if (!timesteps || !range_lo || !range_hi) return fail(PAB_EINVAL, "NULL pointer");
+  if (n_steps < 1) return fail(PAB_EINVAL, "n_steps=%d must be >= 1", n_steps);
+  if (!(t_start >= t_end)) return fail(PAB_EINVAL, "window [%g - %g] starts below its end", t_start, t_end);
+  for (int s = 1; s < n_steps; ++s)
+    if (timesteps[s] > timesteps[s - 1])
+      return fail(PAB_EINVAL, "timesteps increase at step %d (%g after %g)", s, timesteps[s], timesteps[s - 1]);
+  // the list never increases: the steps inside form one run; find its two ends
+  int lo = 0;
+  while (lo < n_steps && timesteps[lo] > t_start) ++lo;
+  int hi = n_steps - 1;
+  while (hi >= 0 && timesteps[hi] < t_end) --hi;
+  if (lo > hi) return 0;
+  *range_lo = lo;
+  *range_hi = hi;
+  return hi - lo + 1;
+}
+
+int pab_preset(int model, int level, int interval[3], double *t_start, double *t_end) {
+  // App. A.2.1: {spatial, temporal, cross} per level, and the window of the model
+  static const int ranges[3][3][3] = {
+      {{2, 4, 6}, {3, 5, 7}, {5, 7, 9}},   // Open-Sora
+      {{2, 4, 6}, {3, 5, 7}, {5, 7, 9}},   // Open-Sora-Plan
+      {{2, 3, 5}, {3, 4, 7}, {4, 6, 9}},   // Latte
+  };
+  static const double window[3][2] = {{930, 450}, {850, 100}, {800, 100}};
+  if (model < 0 || model > 2) return fail(PAB_EINVAL, "model %d is not open_sora(0)/open_sora_plan(1)/latte(2)", model);
+  if (level < 0 || level > 2) return fail(PAB_EINVAL, "level %d outside 0..2", level);
+  if (!interval || !t_start || !t_end) return fail(PAB_EINVAL, "NULL pointer");
+  for (int k = 0; k < 3; ++k) interval[k] = ranges[model][level][k];
+  *t_start = window[model][0];
+  *t_end = window[model][1];
+  return PAB_OK;
+}
+
 size_t pab_workspace_bytes(const pab_config *cfg) {
   if (check_config(cfg) != PAB_OK) return 0;
   int present = 0;

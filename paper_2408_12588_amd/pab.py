@@ -22,7 +22,7 @@ OK, EINVAL, ESTATE, ENOMEM, EDEVICE = 0, -1, -2, -3, -4
 BF16, F32 = 0, 1
 
 EXPORTS = (
-    "pab_schedule", "pab_source_step", "pab_workspace_bytes", "pab_create", "pab_reset", "pab_attention",
+    "pab_schedule", "pab_source_step", "pab_window_from_timesteps", "pab_preset", "pab_workspace_bytes", "pab_create", "pab_reset", "pab_attention",
     "pab_attention_compute", "pab_launch_count", "pab_slot_ptr", "pab_destroy", "pab_last_error",
 )
 
@@ -51,6 +51,11 @@ def _load() -> ctypes.CDLL:
     lib.pab_schedule.argtypes = [ci] * 5
     lib.pab_source_step.restype = ci
     lib.pab_source_step.argtypes = [ci] * 5
+    lib.pab_window_from_timesteps.restype = ci
+    lib.pab_window_from_timesteps.argtypes = [ctypes.POINTER(ctypes.c_double), ci, ctypes.c_double, ctypes.c_double,
+                                              ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    lib.pab_preset.restype = ci
+    lib.pab_preset.argtypes = [ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.pab_workspace_bytes.restype = ctypes.c_size_t
     lib.pab_workspace_bytes.argtypes = [ctypes.POINTER(pab_config)]
     lib.pab_create.restype = ci
@@ -91,6 +96,26 @@ def pab_schedule(kind: int, step: int, range_lo: int, range_hi: int, interval: i
 
 def pab_source_step(kind: int, step: int, range_lo: int, range_hi: int, interval: int) -> int:
     return _check(lib.pab_source_step(kind, step, range_lo, range_hi, interval))
+
+
+OPEN_SORA, OPEN_SORA_PLAN, LATTE = 0, 1, 2
+
+
+def pab_window_from_timesteps(timesteps, t_start: float, t_end: float):
+    """(range_lo, range_hi) of the timestep window on this sampler's steps, or None if no step is inside."""
+    n = len(timesteps)
+    arr = (ctypes.c_double * n)(*[float(t) for t in timesteps])
+    lo, hi = ctypes.c_int(-1), ctypes.c_int(-1)
+    r = _check(lib.pab_window_from_timesteps(arr, n, float(t_start), float(t_end), ctypes.byref(lo), ctypes.byref(hi)))
+    return None if r == 0 else (lo.value, hi.value)
+
+
+def pab_preset(model: int, level: int):
+    """((spatial, temporal, cross) broadcast ranges, t_start, t_end) of one of the paper's settings."""
+    iv = (ctypes.c_int * 3)()
+    a, b = ctypes.c_double(), ctypes.c_double()
+    _check(lib.pab_preset(model, level, iv, ctypes.byref(a), ctypes.byref(b)))
+    return tuple(iv), a.value, b.value
 
 
 def make_config(n_blocks, T, S, L, heads, head_dim, dtype, n_steps, interval, range_lo, range_hi) -> pab_config:

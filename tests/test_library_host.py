@@ -63,6 +63,64 @@ def test_schedule_errors():
             pab.pab_schedule(*args)
 
 
+def test_timestep_window_equals_oracle(golden_timestep_windows):
+    windows, rows, _ = golden_timestep_windows
+    for name, n_steps, first, stride, t_start, t_end, lo, hi in windows:
+        ts = [first - s * stride for s in range(n_steps)]
+        got = pab.pab_window_from_timesteps(ts, t_start, t_end)
+        assert got == orc.window_from_timesteps(ts, t_start, t_end), name
+        assert got == (None if lo < 0 else (lo, hi)), name
+    # the paper's three Open-Sora settings on the first window, row by row
+    name, n_steps, first, stride, t_start, t_end, lo, hi = windows[0]
+    w = pab.pab_window_from_timesteps([first - s * stride for s in range(n_steps)], t_start, t_end)
+    for rname, n, pattern in rows:
+        assert "".join("CR"[pab.pab_schedule(0, s, w[0], w[1], n)] for s in range(n_steps)) == pattern, rname
+    rng = random.Random(3)
+    for _ in range(3000):
+        n = rng.randint(1, 60)
+        ts = sorted((rng.choice([rng.randint(0, 1000), rng.uniform(0, 1000)]) for _ in range(n)), reverse=True)
+        a, b = sorted((rng.uniform(-50, 1050), rng.uniform(-50, 1050)))
+        assert pab.pab_window_from_timesteps(ts, b, a) == orc.window_from_timesteps(ts, b, a)
+
+
+def test_timestep_window_errors():
+    lo, hi = ctypes.c_int(7), ctypes.c_int(8)
+    arr = (ctypes.c_double * 3)(900.0, 500.0, 100.0)
+    f = pab.lib.pab_window_from_timesteps
+    assert f(None, 3, 900.0, 100.0, ctypes.byref(lo), ctypes.byref(hi)) == pab.EINVAL
+    assert f(arr, 0, 900.0, 100.0, ctypes.byref(lo), ctypes.byref(hi)) == pab.EINVAL
+    assert f(arr, 3, 100.0, 900.0, ctypes.byref(lo), ctypes.byref(hi)) == pab.EINVAL
+    assert f(arr, 3, float("nan"), 100.0, ctypes.byref(lo), ctypes.byref(hi)) == pab.EINVAL
+    up = (ctypes.c_double * 3)(100.0, 500.0, 900.0)
+    assert f(up, 3, 900.0, 100.0, ctypes.byref(lo), ctypes.byref(hi)) == pab.EINVAL
+    assert f(arr, 3, 900.0, 100.0, None, ctypes.byref(hi)) == pab.EINVAL
+    assert (lo.value, hi.value) == (7, 8)                      # untouched by failures ...
+    assert f(arr, 3, 450.0, 150.0, ctypes.byref(lo), ctypes.byref(hi)) == 0
+    assert (lo.value, hi.value) == (7, 8)                      # ... and by an empty window
+    assert f(arr, 3, 900.0, 500.0, ctypes.byref(lo), ctypes.byref(hi)) == 2
+    assert (lo.value, hi.value) == (0, 1)
+
+
+def test_presets_are_the_papers_table(golden_timestep_windows):
+    _, _, presets = golden_timestep_windows
+    models = {"open_sora": pab.OPEN_SORA, "open_sora_plan": pab.OPEN_SORA_PLAN, "latte": pab.LATTE}
+    assert len(presets) == 9
+    for model, level, ranges, t_start, t_end in presets:
+        assert pab.pab_preset(models[model], level) == (ranges, t_start, t_end), (model, level)
+    for model in range(3):   # the pyramid (Sec. 2.3): spatial < temporal < cross, and levels get more aggressive
+        prev = (0, 0, 0)
+        for level in range(3):
+            r, _, _ = pab.pab_preset(model, level)
+            assert r[0] < r[1] < r[2]
+            assert all(a >= b for a, b in zip(r, prev)) and r != prev
+            prev = r
+    iv = (ctypes.c_int * 3)()
+    a, b = ctypes.c_double(), ctypes.c_double()
+    for model, level in ((3, 0), (-1, 0), (0, 3), (0, -1)):
+        assert pab.lib.pab_preset(model, level, iv, ctypes.byref(a), ctypes.byref(b)) == pab.EINVAL
+    assert pab.lib.pab_preset(0, 0, None, ctypes.byref(a), ctypes.byref(b)) == pab.EINVAL
+
+
 def test_workspace_bytes():
     cfg = pab.config_of(W.OPENSORA_480P)
     slot = 16 * 1590 * 16 * 72 * 2
