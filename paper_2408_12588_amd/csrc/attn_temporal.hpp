@@ -58,8 +58,12 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
   // value rows of frames that do not exist must be finite: zero the tile once
   for (int idx = lane; idx < RT * DKP / 8; idx += 64) reinterpret_cast<bf16x8 *>(Vs)[idx] = zero8();
 
+  // Workgroup ids go round-robin over the 8 XCDs.  Give every XCD a contiguous run of problems:
+  // four neighbouring heads are 4.5 cache lines, so neighbouring workgroups share a line, and this
+  // way they find it in the same L2.  (The host launches a multiple of 8 workgroups.)
+  const int wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   const int waves_total = gridDim.x * 4;
-  for (int prob = blockIdx.x * 4 + wave; prob < p.n_prob; prob += waves_total) {
+  for (int prob = wg * 4 + wave; prob < p.n_prob; prob += waves_total) {
     const long long off = (long long)prob * D;   // (position*H + head) * D
     const T_ *qg = reinterpret_cast<const T_ *>(p.q) + off;
     const T_ *kg = reinterpret_cast<const T_ *>(p.k) + off;

@@ -78,7 +78,9 @@ int launch_temporal(int T_, int S, int H, const void *q, const void *k, const vo
   p.ss = (long long)S * row;
   p.c = (float)(1.4426950408889634 / std::sqrt((double)D));
   long long grid = (n_prob + 3) / 4;
-  if (grid > 8192) grid = 8192;   // wavefronts loop over problems beyond this
+  // one problem per wavefront measured faster than fewer workgroups that loop; the kernel still
+  // loops, so any grid is correct
+  grid = (grid + 7) / 8 * 8;      // the kernel deals whole eighths of the grid to the XCDs
   if (T_ <= 16)
     hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 16, 16>), dim3((unsigned)grid), dim3(256), 0, st, p);
   else if (T_ <= 24)   // 24 staged rows: three workgroups per CU instead of two
