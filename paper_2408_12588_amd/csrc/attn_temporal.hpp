@@ -27,8 +27,9 @@ struct TemporalParams {
 };
 
 // TP: 16 or 32, the power-of-two tile edge that holds T.  RT: rows of LDS staging per tensor
-// (T <= RT <= TP); fewer rows let more workgroups share a CU.
-template <typename T_, int D, int TP, int RT>
+// (T <= RT <= TP); fewer rows let more workgroups share a CU.  QDIRECT: the q operands are loaded
+// from global memory in MFMA operand layout instead of being staged in LDS like k and v.
+template <typename T_, int D, int TP, int RT, bool QDIRECT>
 __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams p) {
   using HD = HeadDim<D>;
   constexpr int DK = HD::DK, KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH, DKP = HD::DKP;
@@ -36,7 +37,7 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
   constexpr int NR = TP / 2;              // live accumulator registers (keys 16..31 unused when TP == 16)
   constexpr int NM = TP / 16;             // 16-key steps of the second product
   constexpr int OP = D + 8;               // pitch of the output staging rows (elements of T_)
-  constexpr int QK_BYTES = 2 * RT * DKP * 2;
+  constexpr int QK_BYTES = (QDIRECT ? 1 : 2) * RT * DKP * 2;   // k (and q) staging
   constexpr int O_BYTES = RT * OP * (int)sizeof(T_);
   constexpr int A_BYTES = QK_BYTES > O_BYTES ? QK_BYTES : O_BYTES;   // q/k staging, reused for o
   constexpr int V_BYTES = RT * DKP * 2;
@@ -47,8 +48,8 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 31, g = lane >> 5;
   unsigned char *base = smem + wave * WAVE_BYTES;
-  bf16_t *Qs = reinterpret_cast<bf16_t *>(base);                   // [RT][DKP]
-  bf16_t *Ks = Qs + RT * DKP;                                      // [RT][DKP]
+  bf16_t *Qs = reinterpret_cast<bf16_t *>(base);                   // [RT][DKP] (unused with QDIRECT)
+  bf16_t *Ks = QDIRECT ? Qs : Qs + RT * DKP;                       // [RT][DKP]
   T_ *Os = reinterpret_cast<T_ *>(base);                           // [RT][OP], aliases Qs/Ks
   bf16_t *Vs = reinterpret_cast<bf16_t *>(base + A_BYTES);         // [RT][DKP], rows >= T stay zero
 
@@ -79,17 +80,24 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
       const int cidx = lane + 64 * i, t = cidx / CHZ, cc = cidx % CHZ;
       q8[i] = zero8(); k8[i] = zero8(); v8[i] = zero8();
       if (cidx < T * CHZ && cc < CH) {
-        q8[i] = Io<T_>::load8(qg + t * p.ss + 8 * cc);
+        if (!QDIRECT) q8[i] = Io<T_>::load8(qg + t * p.ss + 8 * cc);
         k8[i] = Io<T_>::load8(kg + t * p.ss + 8 * cc);
         v8[i] = Io<T_>::load8(vg + t * p.ss + 8 * cc);
       }
+    }
+    // with QDIRECT the q operands (B: query j = frame j, columns 16 st + 8 g) come straight from memory
+    bf16x8 qd[KSTEPS];
+    if (QDIRECT) {
+      const T_ *qrow_p = qg + (long long)min(j & (TP - 1), T - 1) * p.ss;
+#pragma unroll
+      for (int st = 0; st < KSTEPS; ++st) qd[st] = (16 * st + 8 * g < D) ? Io<T_>::load8(qrow_p + 16 * st + 8 * g) : zero8();
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // previous problem's reads of Os are done
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int cidx = lane + 64 * i, t = cidx / CHZ, cc = cidx % CHZ;
       if (cidx < T * CHZ) {
-        *reinterpret_cast<bf16x8 *>(&Qs[t * DKP + 8 * cc]) = q8[i];
+        if (!QDIRECT) *reinterpret_cast<bf16x8 *>(&Qs[t * DKP + 8 * cc]) = q8[i];
         *reinterpret_cast<bf16x8 *>(&Ks[t * DKP + 8 * cc]) = k8[i];
         if (cc < CH) *reinterpret_cast<bf16x8 *>(&Vs[t * DKP + 8 * cc]) = v8[i];
       }
@@ -105,7 +113,7 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
 #pragma unroll
     for (int st = 0; st < KSTEPS; ++st) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&Ks[krow * DKP + 16 * st + 8 * g]);
-      const bf16x8 qf = *reinterpret_cast<const bf16x8 *>(&Qs[qrow * DKP + 16 * st + 8 * g]);
+      const bf16x8 qf = QDIRECT ? qd[st] : *reinterpret_cast<const bf16x8 *>(&Qs[qrow * DKP + 16 * st + 8 * g]);
       s = mfma32(kf, qf, s);
     }
 

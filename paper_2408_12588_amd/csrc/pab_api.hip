@@ -81,12 +81,14 @@ int launch_temporal(int T_, int S, int H, const void *q, const void *k, const vo
   // one problem per wavefront measured faster than fewer workgroups that loop; the kernel still
   // loops, so any grid is correct
   grid = (grid + 7) / 8 * 8;      // the kernel deals whole eighths of the grid to the XCDs
+  // Clips of more than 16 frames read their q operands straight from memory: the smaller LDS footprint
+  // lets four (24 staged rows) or three (32) workgroups share a CU; at 16 rows staging q measured faster.
   if (T_ <= 16)
-    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 16, 16>), dim3((unsigned)grid), dim3(256), 0, st, p);
-  else if (T_ <= 24)   // 24 staged rows: three workgroups per CU instead of two
-    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 32, 24>), dim3((unsigned)grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 16, 16, false>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  else if (T_ <= 24)
+    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 32, 24, true>), dim3((unsigned)grid), dim3(256), 0, st, p);
   else
-    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 32, 32>), dim3((unsigned)grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((pab::attn_temporal_kernel<T, D, 32, 32, true>), dim3((unsigned)grid), dim3(256), 0, st, p);
   return PAB_OK;
 }
 
