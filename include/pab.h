@@ -170,6 +170,21 @@ int pab_attention(pab_ctx *ctx, int block, int kind, int step, const void *q, co
 int pab_attention_compute(int kind, int dtype, int T, int S, int L, int heads, int head_dim,
                           const void *q, const void *k, const void *v, void *o, void *hip_stream);
 
+/*
+ * A projection of the attention module (paper App. B.5: "qkv proj", "o proj";
+ * App. B.6: q,k,v = proj(x), o = proj(o)): C = A W^T + bias, one kernel launch
+ * on `hip_stream`.  A: [M, K] activations, W: [N, K] weights (row n produces
+ * feature n), bias: [N] or NULL, C: [M, N] written with a row pitch of `ldc`
+ * elements (ldc >= N; ldc > N lets several projections write side by side).
+ * All bf16, dense along their last axis, device pointers, 16-byte aligned;
+ * products accumulate in fp32 and are rounded once.
+ * PAB_EINVAL: NULL or misaligned A / W / C, M or N < 1, K not a positive
+ * multiple of 32, N or ldc not a multiple of 4, ldc < N, or a matrix of more
+ * than 2^31 elements.  PAB_EDEVICE: launch failed.
+ */
+int pab_linear(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
+               void *hip_stream);
+
 /* Kernel launches issued through ctx since pab_create / the last pab_reset
  * (equals the schedule's number of computed calls); -1 if ctx is NULL. */
 long long pab_launch_count(const pab_ctx *ctx);

@@ -15,6 +15,7 @@
 #include "attn_cross_long.hpp"
 #include "attn_temporal.hpp"
 #include "attn_tile.hpp"
+#include "gemm_bias.hpp"
 
 namespace {
 
@@ -362,6 +363,35 @@ int pab_attention_compute(int kind, int dtype, int T, int S, int L, int heads, i
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
     return fail(PAB_EINVAL, "q, k, v, o must be 16-byte aligned");
   return launch_checked(kind, dtype, T, S, L, heads, head_dim, q, k, v, o, static_cast<hipStream_t>(hip_stream));
+}
+
+int pab_linear(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
+               void *hip_stream) {
+  if (!A || !W || !C) return fail(PAB_EINVAL, "A, W and C must not be NULL");
+  if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(C) |
+       reinterpret_cast<uintptr_t>(bias)) & 15u)
+    return fail(PAB_EINVAL, "A, W, bias and C must be 16-byte aligned");
+  if (M < 1 || N < 1) return fail(PAB_EINVAL, "M=%d N=%d must be >= 1", M, N);
+  if (K < 32 || K % 32) return fail(PAB_EINVAL, "K=%d must be a positive multiple of 32", K);
+  if (N % 4 || ldc % 4 || ldc < N) return fail(PAB_EINVAL, "N=%d and ldc=%lld must be multiples of 4, ldc >= N", N, ldc);
+  if ((long long)M * K > 0x7fffffffLL || (long long)N * K > 0x7fffffffLL)
+    return fail(PAB_EINVAL, "matrix too large");
+  pab::GemmParams p;
+  p.A = static_cast<const pab::bf16_t *>(A);
+  p.W = static_cast<const pab::bf16_t *>(W);
+  p.bias = static_cast<const pab::bf16_t *>(bias);
+  p.C = C;
+  p.M = M; p.N = N; p.K = K; p.ldc = ldc;
+  p.n_mt = (M + 127) / 128;
+  p.n_nt = (N + 255) / 256;
+  // an XCD owns every eighth token tile and takes them four at a time over all feature tiles
+  const long long owned = (p.n_mt + 7) / 8, groups = (owned + 3) / 4;
+  const long long grid = 8 * groups * 4 * p.n_nt;
+  if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "matrix too large");
+  hipLaunchKernelGGL((pab::gemm_bias_kernel<3>), dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(hip_stream), p);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+  return PAB_OK;
 }
 
 long long pab_launch_count(const pab_ctx *ctx) { return ctx ? ctx->launches : -1; }

@@ -23,7 +23,7 @@ BF16, F32 = 0, 1
 
 EXPORTS = (
     "pab_schedule", "pab_source_step", "pab_window_from_timesteps", "pab_preset", "pab_workspace_bytes", "pab_create", "pab_reset", "pab_attention",
-    "pab_attention_compute", "pab_launch_count", "pab_slot_ptr", "pab_destroy", "pab_last_error",
+    "pab_attention_compute", "pab_linear", "pab_launch_count", "pab_slot_ptr", "pab_destroy", "pab_last_error",
 )
 
 
@@ -66,6 +66,8 @@ def _load() -> ctypes.CDLL:
     lib.pab_attention.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, ctypes.POINTER(vp)]
     lib.pab_attention_compute.restype = ci
     lib.pab_attention_compute.argtypes = [ci] * 7 + [vp] * 5
+    lib.pab_linear.restype = ci
+    lib.pab_linear.argtypes = [ci, ci, ci, vp, vp, vp, vp, ctypes.c_longlong, vp]
     lib.pab_launch_count.restype = ctypes.c_longlong
     lib.pab_launch_count.argtypes = [vp]
     lib.pab_slot_ptr.restype = vp
@@ -233,4 +235,30 @@ def pab_attention_compute(kind: int, q, k, v, out=None, L: int | None = None, st
         out = torch.empty_like(q)
     _check(lib.pab_attention_compute(kind, dtype, T, S, L, H, D, _ptr(q), _ptr(k), _ptr(v), _ptr(out),
                                      _stream(stream)))
+    return out
+
+
+def pab_linear(a, w, bias=None, out=None, stream=None):
+    """out = a @ w.T + bias (bf16).  a ``[..., K]`` dense, w ``[N, K]``, bias ``[N]`` or None.  ``out`` may be a
+    view whose last axis is dense and whose rows are ``out.stride(-2)`` apart (several projections side by side)."""
+    if a.dtype != torch.bfloat16 or w.dtype != torch.bfloat16 or (bias is not None and bias.dtype != torch.bfloat16):
+        raise ValueError("pab_linear takes bf16 tensors")
+    if not a.is_contiguous() or not w.is_contiguous():
+        raise ValueError("a and w must be contiguous")
+    K = a.shape[-1]
+    N = w.shape[0]
+    M = a.numel() // K
+    if w.shape[1] != K:
+        raise ValueError("w must be [N, K]")
+    if out is None:
+        out = torch.empty(a.shape[:-1] + (N,), device=a.device, dtype=torch.bfloat16)
+    if out.stride(-1) != 1 or out.shape[-1] != N or out.numel() != M * N:
+        raise ValueError("out must be [..., N] with a dense last axis")
+    if not out.is_cuda:
+        raise ValueError("libpab takes device tensors")
+    ldc = out.stride(-2) if out.dim() >= 2 else N
+    if out.dim() > 2 and any(out.stride(i) != out.stride(i + 1) * out.shape[i + 1] for i in range(out.dim() - 2)):
+        raise ValueError("the leading axes of out must collapse into one row index")
+    _check(lib.pab_linear(M, N, K, _ptr(a), _ptr(w), _ptr(bias) if bias is not None else None, out.data_ptr(), ldc,
+                          _stream(stream)))
     return out
