@@ -185,6 +185,70 @@ int pab_attention_compute(int kind, int dtype, int T, int S, int L, int heads, i
 int pab_linear(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
                void *hip_stream);
 
+/*
+ * The paper broadcasts the output of the whole attention MODULE, so that a
+ * reused step also skips what surrounds the attention operation (App. B.6:
+ * x -> q,k,v = proj(x) -> q,k = pos_emb(layer_norm(q,k)) -> o = attn(q,k,v)
+ * -> o = proj(o); App. B.5 lists the parts: layernorm1, modulate, qkv proj,
+ * layernorm2, pos emb, attn, o proj).  The three calls below are that module
+ * with its output as the cached object; they use the same context, schedule
+ * and cache slots as pab_attention (a slot holds [T, S, C], C = heads *
+ * head_dim, the same bytes as an attention output).  bf16 only.
+ *
+ * Weights of one module: device pointers, bf16, dense.
+ *   spatial / temporal:  h = LayerNorm_C(x) * (1 + scale) + shift          shift, scale [C]
+ *                        [q | k | v] = h w_qkv^T + b_qkv                    w_qkv [3C, C], b_qkv [3C] or NULL,
+ *                                                                           each of q, k, v laid out [heads, D]
+ *                        q, k = LayerNorm_D(.) * gamma + beta               gamma_q, beta_q, gamma_k, beta_k [D]
+ *                        temporal only: rotary embedding of q, k by the frame index (pairs (2i, 2i+1),
+ *                        angle t * 10000^(-2i/D))
+ *                        y = attention(q, k, v) w_o^T + b_o                 w_o [C, C], b_o [C] or NULL
+ *   cross:               q = x w_qkv^T + b_qkv                              w_qkv [C, C], b_qkv [C] or NULL
+ *                        [k | v] = text w_kv^T + b_kv                       w_kv [2C, C], b_kv [2C] or NULL
+ *                        y = attention(q, k, v) w_o^T + b_o                 (shift .. beta_k unused)
+ * LayerNorms use the biased variance and eps = 1e-6.  C must be a multiple
+ * of 32 and at most 2048.
+ */
+typedef struct pab_module_weights {
+  const void *shift, *scale;
+  const void *w_qkv, *b_qkv;
+  const void *gamma_q, *beta_q, *gamma_k, *beta_k;
+  const void *w_kv, *b_kv;
+  const void *w_o, *b_o;
+} pab_module_weights;
+
+/*
+ * Bytes of device scratch a computed module call of `cfg` needs (four planes
+ * of max(T*S, L) * C bf16 elements, each rounded up to 256 bytes): the
+ * modulated input / attention output, q, k and v.  The caller allocates it
+ * once; calls on one stream may share it.  0 if cfg is NULL or invalid.
+ */
+size_t pab_module_scratch_bytes(const pab_config *cfg);
+
+/*
+ * One module, no schedule and no cache: x [T, S, C] (and text [L, C] for
+ * cross attention) -> out [T, S, C], five kernel launches (four for cross)
+ * on `hip_stream`.  `scratch` must be 256-byte aligned and at least
+ * pab_module_scratch_bytes() of the same shape long.
+ * PAB_EINVAL: bad kind / shape / head_dim, C not a multiple of 32 or > 2048,
+ * NULL or misaligned x / out / scratch / a weight the kind needs, text missing
+ * for cross.  PAB_ENOMEM: scratch too small.  PAB_EDEVICE: a launch failed.
+ */
+int pab_module_compute(int kind, int T, int S, int L, int heads, int head_dim, const void *x, const void *text,
+                       const pab_module_weights *w, void *scratch, size_t scratch_bytes, void *out,
+                       void *hip_stream);
+
+/*
+ * pab_attention at module level (paper Sec. 2.3, Eq. 1 with the module output
+ * as Y): on a computed step runs the module into cache slot (block, kind), on
+ * a reused step launches nothing and reads nothing (x, text, w, scratch may be
+ * NULL).  *out, return value and errors as pab_attention, plus those of
+ * pab_module_compute; PAB_EINVAL if the context's dtype is not bf16.
+ */
+int pab_module_attention(pab_ctx *ctx, int block, int kind, int step, const void *x, const void *text,
+                         const pab_module_weights *w, void *scratch, size_t scratch_bytes, void *hip_stream,
+                         const void **out);
+
 /* Kernel launches issued through ctx since pab_create / the last pab_reset
  * (equals the schedule's number of computed calls); -1 if ctx is NULL. */
 long long pab_launch_count(const pab_ctx *ctx);

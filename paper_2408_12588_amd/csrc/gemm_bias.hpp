@@ -28,9 +28,11 @@ struct GemmParams {
   const bf16_t *A;      // [M, K]
   const bf16_t *W;      // [N, K]
   const bf16_t *bias;   // [N] or nullptr
-  void *C;              // [M, ldc] bf16
+  void *C;              // bf16; feature n of token m goes to C[(n / n_split) * plane_stride + m * ldc + n % n_split]
   int M, N, K;
-  long long ldc;        // row pitch of C in elements (>= N)
+  long long ldc;        // row pitch of C in elements
+  int n_split;          // features per output plane (N: one plane; a multiple of 4)
+  long long plane_stride;
   int n_mt, n_nt;       // token / feature tiles
 };
 
@@ -140,6 +142,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bias_kernel(const GemmParams p) {
     for (int rq = 0; rq < 4; ++rq) {
       const int n = n0 + wn * 128 + b * 32 + 8 * rq + 4 * g;
       if (n >= N) continue;
+      const int plane = n / p.n_split;
+      bf16_t *Cn = C + plane * p.plane_stride + (n - plane * p.n_split);
       float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
       if (p.bias) {
         const bf16x4 b4 = *reinterpret_cast<const bf16x4 *>(p.bias + n);
@@ -150,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bias_kernel(const GemmParams p) {
       for (int a = 0; a < 2; ++a) {
         const int m = m0 + wm * 64 + a * 32 + j;
         if (m < M)
-          Io<bf16_t>::store4(C + (long long)m * p.ldc + n, acc[a][b][4 * rq] + bv[0], acc[a][b][4 * rq + 1] + bv[1],
+          Io<bf16_t>::store4(Cn + (long long)m * p.ldc, acc[a][b][4 * rq] + bv[0], acc[a][b][4 * rq + 1] + bv[1],
                              acc[a][b][4 * rq + 2] + bv[2], acc[a][b][4 * rq + 3] + bv[3]);
       }
     }

@@ -16,6 +16,7 @@
 #include "attn_temporal.hpp"
 #include "attn_tile.hpp"
 #include "gemm_bias.hpp"
+#include "module_rowwise.hpp"
 
 namespace {
 
@@ -223,6 +224,142 @@ struct pab_ctx {
   long long launches;
 };
 
+namespace {
+
+// ---- what the two cached entry points share: validate the cell, take the decision of Eq. 1,
+//      find the slot; after a successful launch (or on reuse) record the step ----
+int schedule_cell(pab_ctx *ctx, int block, int kind, int step, void **slot) {
+  const pab_config &c = ctx->cfg;
+  if (!kind_ok(kind)) return fail(PAB_EINVAL, "kind %d is not spatial(0)/temporal(1)/cross(2)", kind);
+  if (c.interval[kind] == 0) return fail(PAB_EINVAL, "kind %d is absent from this config (interval 0)", kind);
+  if (block < 0 || block >= c.n_blocks) return fail(PAB_EINVAL, "block %d outside [0, %d)", block, c.n_blocks);
+  if (step < 0 || step >= c.n_steps) return fail(PAB_EINVAL, "step %d outside [0, %d)", step, c.n_steps);
+  const size_t cell = (size_t)block * 3 + kind;
+  if (step < ctx->last_step[cell])
+    return fail(PAB_ESTATE, "step %d after step %d for block %d kind %d without pab_reset", step,
+                ctx->last_step[cell], block, kind);
+  const int decision = pab_schedule(kind, step, c.range_lo, c.range_hi, c.interval[kind]);
+  if (decision < 0) return decision;
+  if (decision == PAB_REUSE && ctx->computed_step[cell] < 0)
+    return fail(PAB_ESTATE, "reuse at step %d but block %d kind %d was never computed", step, block, kind);
+  *slot = const_cast<void *>(pab_slot_ptr(ctx, block, kind));
+  return decision;
+}
+
+void commit_cell(pab_ctx *ctx, int block, int kind, int step, int decision) {
+  const size_t cell = (size_t)block * 3 + kind;
+  if (decision == PAB_COMPUTE) {
+    ctx->computed_step[cell] = step;
+    ctx->launches++;
+  }
+  ctx->last_step[cell] = step;
+}
+
+// ---- the attention module (paper App. B.5 / B.6) ----
+size_t module_plane_bytes(int T, int S, int L, int H, int D) {
+  const long long rows = (long long)T * S > L ? (long long)T * S : L;
+  return ((size_t)rows * H * D * 2 + 255) / 256 * 256;
+}
+
+int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
+                int n_split, long long plane_stride, hipStream_t st) {
+  if (!A || !W || !C) return fail(PAB_EINVAL, "A, W and C must not be NULL");
+  if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(C) |
+       reinterpret_cast<uintptr_t>(bias)) & 15u)
+    return fail(PAB_EINVAL, "A, W, bias and C must be 16-byte aligned");
+  if (M < 1 || N < 1) return fail(PAB_EINVAL, "M=%d N=%d must be >= 1", M, N);
+  if (K < 32 || K % 32) return fail(PAB_EINVAL, "K=%d must be a positive multiple of 32", K);
+  if (N % 4 || ldc % 4 || n_split % 4 || plane_stride % 4)
+    return fail(PAB_EINVAL, "N=%d and ldc=%lld must be multiples of 4", N, ldc);
+  if ((long long)M * K > 0x7fffffffLL || (long long)N * K > 0x7fffffffLL)
+    return fail(PAB_EINVAL, "matrix too large");
+  pab::GemmParams p;
+  p.A = static_cast<const pab::bf16_t *>(A);
+  p.W = static_cast<const pab::bf16_t *>(W);
+  p.bias = static_cast<const pab::bf16_t *>(bias);
+  p.C = C;
+  p.M = M; p.N = N; p.K = K; p.ldc = ldc;
+  p.n_split = n_split; p.plane_stride = plane_stride;
+  p.n_mt = (M + 127) / 128;
+  p.n_nt = (N + 255) / 256;
+  // an XCD owns every eighth token tile and takes them four at a time over all feature tiles
+  const long long owned = (p.n_mt + 7) / 8, groups = (owned + 3) / 4;
+  const long long grid = 8 * groups * 4 * p.n_nt;
+  if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "matrix too large");
+  hipLaunchKernelGGL((pab::gemm_bias_kernel<3>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+  return PAB_OK;
+}
+
+int launch_ln_modulate(int n_tok, int C, const void *x, const void *shift, const void *scale, void *h, hipStream_t st) {
+  pab::LnModParams p;
+  p.x = static_cast<const pab::bf16_t *>(x);
+  p.shift = static_cast<const pab::bf16_t *>(shift);
+  p.scale = static_cast<const pab::bf16_t *>(scale);
+  p.h = static_cast<pab::bf16_t *>(h);
+  p.n_tok = n_tok; p.C = C; p.eps = 1e-6f;
+  const dim3 grid((unsigned)((n_tok + 3) / 4)), block(256);
+  switch ((C + 511) / 512) {
+    case 1: hipLaunchKernelGGL((pab::ln_modulate_kernel<1>), grid, block, 0, st, p); break;
+    case 2: hipLaunchKernelGGL((pab::ln_modulate_kernel<2>), grid, block, 0, st, p); break;
+    case 3: hipLaunchKernelGGL((pab::ln_modulate_kernel<3>), grid, block, 0, st, p); break;
+    case 4: hipLaunchKernelGGL((pab::ln_modulate_kernel<4>), grid, block, 0, st, p); break;
+    default: return fail(PAB_EINVAL, "hidden size %d beyond 2048", C);
+  }
+  return PAB_OK;
+}
+
+int launch_qk_norm(int n_tok, int H, int D, int S, int rope, void *q, void *k, const pab_module_weights *w, hipStream_t st) {
+  pab::QkNormParams p;
+  p.q = static_cast<pab::bf16_t *>(q);
+  p.k = static_cast<pab::bf16_t *>(k);
+  p.gq = static_cast<const pab::bf16_t *>(w->gamma_q); p.bq = static_cast<const pab::bf16_t *>(w->beta_q);
+  p.gk = static_cast<const pab::bf16_t *>(w->gamma_k); p.bk = static_cast<const pab::bf16_t *>(w->beta_k);
+  p.n_tok = n_tok; p.H = H; p.S = S; p.rope = rope; p.eps = 1e-6f;
+  p.log2_base = 13.287712379549449f;   // log2(10000)
+  const long long waves = ((long long)n_tok * H + 63) / 64;
+  const dim3 grid((unsigned)((waves + 3) / 4), 2), block(256);
+  if (D == 72) hipLaunchKernelGGL((pab::qk_norm_rope_kernel<72>), grid, block, 0, st, p);
+  else hipLaunchKernelGGL((pab::qk_norm_rope_kernel<32>), grid, block, 0, st, p);
+  return PAB_OK;
+}
+
+int launch_module(int kind, int T, int S, int L, int H, int D, const void *x, const void *text,
+                  const pab_module_weights *w, void *scratch, size_t scratch_bytes, void *out, hipStream_t st) {
+  const int C = H * D;
+  const long long tok = (long long)T * S;
+  if (C % 32) return fail(PAB_EINVAL, "hidden size heads*head_dim=%d must be a multiple of 32", C);
+  if (tok > 0x7fffffffLL / C) return fail(PAB_EINVAL, "too many tokens");
+  if (!x || !w || !scratch) return fail(PAB_EINVAL, "x, weights and scratch must be non-NULL on a computed step");
+  if (!aligned16(x) || (reinterpret_cast<uintptr_t>(scratch) & 255u)) return fail(PAB_EINVAL, "x must be 16-byte, scratch 256-byte aligned");
+  const size_t plane = module_plane_bytes(T, S, L, H, D);
+  if (scratch_bytes < 4 * plane) return fail(PAB_ENOMEM, "scratch of %zu bytes, need %zu", scratch_bytes, 4 * plane);
+  unsigned char *s0 = static_cast<unsigned char *>(scratch);
+  void *p_ho = s0, *p_q = s0 + plane, *p_k = s0 + 2 * plane, *p_v = s0 + 3 * plane;
+  const long long plane_elems = (long long)(plane / 2);
+  int rc;
+  if (kind == PAB_CROSS) {
+    if (!text || !aligned16(text)) return fail(PAB_EINVAL, "cross attention needs the text tokens, 16-byte aligned");
+    if (!w->w_qkv || !w->w_kv || !w->w_o) return fail(PAB_EINVAL, "cross module needs w_qkv (queries), w_kv and w_o");
+    if ((rc = launch_gemm((int)tok, C, C, x, w->w_qkv, w->b_qkv, p_q, C, C, 0, st)) != PAB_OK) return rc;
+    if ((rc = launch_gemm(L, 2 * C, C, text, w->w_kv, w->b_kv, p_k, C, C, plane_elems, st)) != PAB_OK) return rc;
+  } else {
+    if (!w->shift || !w->scale || !w->w_qkv || !w->gamma_q || !w->beta_q || !w->gamma_k || !w->beta_k || !w->w_o)
+      return fail(PAB_EINVAL, "self-attention module needs shift, scale, w_qkv, gamma/beta of q and k, w_o");
+    if ((rc = launch_ln_modulate((int)tok, C, x, w->shift, w->scale, p_ho, st)) != PAB_OK) return rc;
+    if ((rc = launch_gemm((int)tok, 3 * C, C, p_ho, w->w_qkv, w->b_qkv, p_q, C, C, plane_elems, st)) != PAB_OK) return rc;
+    if ((rc = launch_qk_norm((int)tok, H, D, S, kind == PAB_TEMPORAL, p_q, p_k, w, st)) != PAB_OK) return rc;
+  }
+  if ((rc = launch_checked(kind, PAB_BF16, T, S, L, H, D, p_q, p_k, p_v, p_ho, st)) != PAB_OK) return rc;
+  if ((rc = launch_gemm((int)tok, C, C, p_ho, w->w_o, w->b_o, out, C, C, 0, st)) != PAB_OK) return rc;
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+  return PAB_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 int pab_schedule(int kind, int step, int range_lo, int range_hi, int interval) {
@@ -327,30 +464,17 @@ int pab_attention(pab_ctx *ctx, int block, int kind, int step, const void *q, co
   if (!out) return fail(PAB_EINVAL, "out is NULL");
   *out = nullptr;
   const pab_config &c = ctx->cfg;
-  if (!kind_ok(kind)) return fail(PAB_EINVAL, "kind %d is not spatial(0)/temporal(1)/cross(2)", kind);
-  if (c.interval[kind] == 0) return fail(PAB_EINVAL, "kind %d is absent from this config (interval 0)", kind);
-  if (block < 0 || block >= c.n_blocks) return fail(PAB_EINVAL, "block %d outside [0, %d)", block, c.n_blocks);
-  if (step < 0 || step >= c.n_steps) return fail(PAB_EINVAL, "step %d outside [0, %d)", step, c.n_steps);
-  const size_t cell = (size_t)block * 3 + kind;
-  if (step < ctx->last_step[cell])
-    return fail(PAB_ESTATE, "step %d after step %d for block %d kind %d without pab_reset", step,
-                ctx->last_step[cell], block, kind);
-  const int decision = pab_schedule(kind, step, c.range_lo, c.range_hi, c.interval[kind]);
+  void *slot = nullptr;
+  const int decision = schedule_cell(ctx, block, kind, step, &slot);
   if (decision < 0) return decision;
-  void *slot = const_cast<void *>(pab_slot_ptr(ctx, block, kind));
-  if (decision == PAB_REUSE) {
-    if (ctx->computed_step[cell] < 0)
-      return fail(PAB_ESTATE, "reuse at step %d but block %d kind %d was never computed", step, block, kind);
-  } else {
+  if (decision == PAB_COMPUTE) {
     if (!q || !k || !v) return fail(PAB_EINVAL, "q, k, v must be non-NULL on a computed step");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return fail(PAB_EINVAL, "q, k, v must be 16-byte aligned");
     const int rc = launch_checked(kind, c.dtype, c.T, c.S, c.L, c.heads, c.head_dim, q, k, v, slot,
                                   static_cast<hipStream_t>(hip_stream));
     if (rc != PAB_OK) return rc;
-    ctx->computed_step[cell] = step;
-    ctx->launches++;
   }
-  ctx->last_step[cell] = step;
+  commit_cell(ctx, block, kind, step, decision);
   *out = slot;
   return decision;
 }
@@ -367,31 +491,44 @@ int pab_attention_compute(int kind, int dtype, int T, int S, int L, int heads, i
 
 int pab_linear(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
                void *hip_stream) {
-  if (!A || !W || !C) return fail(PAB_EINVAL, "A, W and C must not be NULL");
-  if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(C) |
-       reinterpret_cast<uintptr_t>(bias)) & 15u)
-    return fail(PAB_EINVAL, "A, W, bias and C must be 16-byte aligned");
-  if (M < 1 || N < 1) return fail(PAB_EINVAL, "M=%d N=%d must be >= 1", M, N);
-  if (K < 32 || K % 32) return fail(PAB_EINVAL, "K=%d must be a positive multiple of 32", K);
-  if (N % 4 || ldc % 4 || ldc < N) return fail(PAB_EINVAL, "N=%d and ldc=%lld must be multiples of 4, ldc >= N", N, ldc);
-  if ((long long)M * K > 0x7fffffffLL || (long long)N * K > 0x7fffffffLL)
-    return fail(PAB_EINVAL, "matrix too large");
-  pab::GemmParams p;
-  p.A = static_cast<const pab::bf16_t *>(A);
-  p.W = static_cast<const pab::bf16_t *>(W);
-  p.bias = static_cast<const pab::bf16_t *>(bias);
-  p.C = C;
-  p.M = M; p.N = N; p.K = K; p.ldc = ldc;
-  p.n_mt = (M + 127) / 128;
-  p.n_nt = (N + 255) / 256;
-  // an XCD owns every eighth token tile and takes them four at a time over all feature tiles
-  const long long owned = (p.n_mt + 7) / 8, groups = (owned + 3) / 4;
-  const long long grid = 8 * groups * 4 * p.n_nt;
-  if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "matrix too large");
-  hipLaunchKernelGGL((pab::gemm_bias_kernel<3>), dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(hip_stream), p);
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
-  return PAB_OK;
+  if (ldc < N) return fail(PAB_EINVAL, "ldc=%lld must be >= N=%d", ldc, N);
+  return launch_gemm(M, N, K, A, W, bias, C, ldc, N, 0, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t pab_module_scratch_bytes(const pab_config *cfg) {
+  if (check_config(cfg) != PAB_OK) return 0;
+  return 4 * module_plane_bytes(cfg->T, cfg->S, cfg->L, cfg->heads, cfg->head_dim);
+}
+
+int pab_module_compute(int kind, int T, int S, int L, int heads, int head_dim, const void *x, const void *text,
+                       const pab_module_weights *w, void *scratch, size_t scratch_bytes, void *out,
+                       void *hip_stream) {
+  const int rc = check_shape(kind, PAB_BF16, T, S, L, heads, head_dim);
+  if (rc != PAB_OK) return rc;
+  if (!out || !aligned16(out)) return fail(PAB_EINVAL, "out must be non-NULL and 16-byte aligned");
+  return launch_module(kind, T, S, L, heads, head_dim, x, text, w, scratch, scratch_bytes, out,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int pab_module_attention(pab_ctx *ctx, int block, int kind, int step, const void *x, const void *text,
+                         const pab_module_weights *w, void *scratch, size_t scratch_bytes, void *hip_stream,
+                         const void **out) {
+  if (!ctx) return fail(PAB_EINVAL, "ctx is NULL");
+  if (!out) return fail(PAB_EINVAL, "out is NULL");
+  *out = nullptr;
+  const pab_config &c = ctx->cfg;
+  if (c.dtype != PAB_BF16) return fail(PAB_EINVAL, "the module path takes bf16 configs only");
+  void *slot = nullptr;
+  const int decision = schedule_cell(ctx, block, kind, step, &slot);
+  if (decision < 0) return decision;
+  if (decision == PAB_COMPUTE) {
+    const int rc = launch_module(kind, c.T, c.S, c.L, c.heads, c.head_dim, x, text, w, scratch, scratch_bytes, slot,
+                                 static_cast<hipStream_t>(hip_stream));
+    if (rc != PAB_OK) return rc;
+  }
+  commit_cell(ctx, block, kind, step, decision);
+  *out = slot;
+  return decision;
 }
 
 long long pab_launch_count(const pab_ctx *ctx) { return ctx ? ctx->launches : -1; }

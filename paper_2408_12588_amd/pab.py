@@ -23,7 +23,8 @@ BF16, F32 = 0, 1
 
 EXPORTS = (
     "pab_schedule", "pab_source_step", "pab_window_from_timesteps", "pab_preset", "pab_workspace_bytes", "pab_create", "pab_reset", "pab_attention",
-    "pab_attention_compute", "pab_linear", "pab_launch_count", "pab_slot_ptr", "pab_destroy", "pab_last_error",
+    "pab_attention_compute", "pab_linear", "pab_module_scratch_bytes", "pab_module_compute", "pab_module_attention",
+    "pab_launch_count", "pab_slot_ptr", "pab_destroy", "pab_last_error",
 )
 
 
@@ -38,6 +39,11 @@ class pab_config(ctypes.Structure):
                 ("heads", ctypes.c_int), ("head_dim", ctypes.c_int), ("dtype", ctypes.c_int),
                 ("n_steps", ctypes.c_int), ("interval", ctypes.c_int * 3),
                 ("range_lo", ctypes.c_int), ("range_hi", ctypes.c_int)]
+
+
+class pab_module_weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("shift", "scale", "w_qkv", "b_qkv", "gamma_q", "beta_q", "gamma_k",
+                                               "beta_k", "w_kv", "b_kv", "w_o", "b_o")]
 
 
 def _load() -> ctypes.CDLL:
@@ -68,6 +74,13 @@ def _load() -> ctypes.CDLL:
     lib.pab_attention_compute.argtypes = [ci] * 7 + [vp] * 5
     lib.pab_linear.restype = ci
     lib.pab_linear.argtypes = [ci, ci, ci, vp, vp, vp, vp, ctypes.c_longlong, vp]
+    lib.pab_module_scratch_bytes.restype = ctypes.c_size_t
+    lib.pab_module_scratch_bytes.argtypes = [ctypes.POINTER(pab_config)]
+    lib.pab_module_compute.restype = ci
+    lib.pab_module_compute.argtypes = [ci] * 6 + [vp, vp, ctypes.POINTER(pab_module_weights), vp, ctypes.c_size_t, vp, vp]
+    lib.pab_module_attention.restype = ci
+    lib.pab_module_attention.argtypes = [vp, ci, ci, ci, vp, vp, ctypes.POINTER(pab_module_weights), vp,
+                                         ctypes.c_size_t, vp, ctypes.POINTER(vp)]
     lib.pab_launch_count.restype = ctypes.c_longlong
     lib.pab_launch_count.argtypes = [vp]
     lib.pab_slot_ptr.restype = vp
@@ -186,6 +199,14 @@ class PabContext:
                                        ctypes.byref(out)))
         return dec, out.value
 
+    def pab_module_attention(self, block: int, kind: int, step: int, x, text, w, scratch, stream=None):
+        """Module-level call -> (decision, device pointer of the slot holding the module output [T, S, C])."""
+        out = ctypes.c_void_p()
+        dec = _check(lib.pab_module_attention(
+            self._h, block, kind, step, _ptr(x), _ptr(text), ctypes.byref(w) if w is not None else None,
+            _ptr(scratch), scratch.numel() if scratch is not None else 0, _stream(stream), ctypes.byref(out)))
+        return dec, out.value
+
     def slot_tensor(self, block: int, kind: int) -> torch.Tensor:
         """View of cache slot (block, kind) inside the workspace tensor (no copy)."""
         p = lib.pab_slot_ptr(self._h, block, kind)
@@ -261,4 +282,44 @@ def pab_linear(a, w, bias=None, out=None, stream=None):
         raise ValueError("the leading axes of out must collapse into one row index")
     _check(lib.pab_linear(M, N, K, _ptr(a), _ptr(w), _ptr(bias) if bias is not None else None, out.data_ptr(), ldc,
                           _stream(stream)))
+    return out
+
+
+def module_weights(**tensors):
+    """pab_module_weights from bf16 device tensors given by field name; keeps them alive on the result."""
+    w = pab_module_weights()
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        if t.dtype != torch.bfloat16:
+            raise ValueError("module weights are bf16")
+        setattr(w, name, _ptr(t))
+    w._keep = tensors
+    return w
+
+
+def pab_module_scratch_bytes(cfg: pab_config) -> int:
+    n = lib.pab_module_scratch_bytes(ctypes.byref(cfg))
+    if n == 0:
+        raise PabError(EINVAL, pab_last_error())
+    return n
+
+
+def module_scratch(T, S, L, heads, head_dim, device):
+    """A scratch tensor (uint8, 256-byte aligned by the allocator) for module calls of this shape."""
+    cfg = make_config(1, T, S, max(L, 1), heads, head_dim, BF16, 1, (1, 1, 1), 0, 0)
+    return torch.empty(pab_module_scratch_bytes(cfg), dtype=torch.uint8, device=device)
+
+
+def pab_module_compute(kind: int, x, text, w: pab_module_weights, heads: int, scratch=None, out=None, stream=None):
+    """One attention module without schedule or cache: x ``[T, S, C]`` (text ``[L, C]`` for cross) -> ``[T, S, C]``."""
+    T, S, C = x.shape
+    D = C // heads
+    L = text.shape[0] if text is not None else 0
+    if scratch is None:
+        scratch = module_scratch(T, S, L, heads, D, x.device)
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib.pab_module_compute(kind, T, S, L, heads, D, _ptr(x), _ptr(text) if text is not None else None,
+                                  ctypes.byref(w), _ptr(scratch), scratch.numel(), _ptr(out), _stream(stream)))
     return out

@@ -83,3 +83,137 @@ def test_linear_argument_errors(pab):
     assert f(8, 8, 64, a.data_ptr(), w.data_ptr(), None, c.data_ptr(), 4, None) == pab.EINVAL      # ldc < N
     assert f(8, 8, 64, a.data_ptr() + 2, w.data_ptr(), None, c.data_ptr(), 8, None) == pab.EINVAL  # alignment
     assert f(0, 8, 64, a.data_ptr(), w.data_ptr(), None, c.data_ptr(), 8, None) == pab.EINVAL
+
+
+# ---- the whole module -----------------------------------------------------------------------
+# Bound: the attention operation is held to 1e-2 * max|V|; around it sit projections whose inputs
+# and outputs are stored in bf16 (2^-9 relative each, averaging out over the K = C terms of a
+# product) and whose weights have rows of about unit norm, so the module output carries an
+# error of the size of the attention error: 2e-2 * max|y| leaves a factor of two.
+TOL_MODULE = 2e-2
+
+
+def self_weights(C, heads, seed):
+    D = C // heads
+    return dict(shift=bf16_randn((C,), seed + 1, 0.3), scale=bf16_randn((C,), seed + 2, 0.3),
+                w_qkv=bf16_randn((3 * C, C), seed + 3, 1.0 / math.sqrt(C)), b_qkv=bf16_randn((3 * C,), seed + 4, 0.1),
+                gamma_q=(1.0 + 0.2 * bf16_randn((D,), seed + 5).float()).to(torch.bfloat16), beta_q=bf16_randn((D,), seed + 6, 0.2),
+                gamma_k=(1.0 + 0.2 * bf16_randn((D,), seed + 7).float()).to(torch.bfloat16), beta_k=bf16_randn((D,), seed + 8, 0.2),
+                w_o=bf16_randn((C, C), seed + 9, 1.0 / math.sqrt(C)), b_o=bf16_randn((C,), seed + 10, 0.1))
+
+
+def oracle_self(kind, x, w, heads):
+    return mo.self_attention_module(kind, f64(x), f64(w["shift"]), f64(w["scale"]), f64(w["w_qkv"]), f64(w["b_qkv"]),
+                                    f64(w["gamma_q"]), f64(w["beta_q"]), f64(w["gamma_k"]), f64(w["beta_k"]),
+                                    f64(w["w_o"]), f64(w["b_o"]), heads)
+
+
+def check_module(got, want, what):
+    got = f64(got)
+    assert got.shape == want.shape and np.isfinite(got).all(), what
+    err = np.abs(got - want).max()
+    bound = TOL_MODULE * np.abs(want).max()
+    assert err <= bound, "%s: max abs err %.3e > %.3e" % (what, err, bound)
+    return err / np.abs(want).max()
+
+
+MODULE_SHAPES = [
+    # kind, T, S, heads, D
+    (0, 2, 150, 4, 72),     # spatial: ragged token tail for every kernel of the chain
+    (0, 3, 64, 4, 32),      # head dim 32, hidden size 128
+    (1, 16, 21, 4, 72),     # temporal with rotary embedding, 16 frames
+    (1, 17, 9, 8, 32),      # 17 frames (32-row temporal kernel), hidden size 256
+    (1, 1, 40, 4, 72),      # one frame: attention is the identity on v, frame index 0 turns nothing
+]
+
+
+@pytest.mark.parametrize("kind,T,S,heads,D", MODULE_SHAPES)
+def test_self_module_matches_oracle(pab, kind, T, S, heads, D):
+    print("module case", kind, T, S, heads, D, flush=True)
+    C = heads * D
+    x = bf16_randn((T, S, C), 500 + T + S)
+    w = self_weights(C, heads, 600 + 10 * kind)
+    wd = pab.module_weights(**{k: v.to(DEV) for k, v in w.items()})
+    out = pab.pab_module_compute(kind, x.to(DEV), None, wd, heads)
+    torch.cuda.synchronize()
+    rel = check_module(out, oracle_self(kind, x, w, heads), "self module kind %d" % kind)
+    print("   relative max error %.2e" % rel, flush=True)
+
+
+@pytest.mark.parametrize("T,S,L,heads,D", [(2, 100, 120, 4, 72), (1, 33, 300, 4, 72), (2, 50, 16, 4, 32)])
+def test_cross_module_matches_oracle(pab, T, S, L, heads, D):
+    print("cross module case", T, S, L, heads, D, flush=True)
+    C = heads * D
+    x, text = bf16_randn((T, S, C), 700 + S), bf16_randn((L, C), 701 + L)
+    w = dict(w_qkv=bf16_randn((C, C), 710, 1.0 / math.sqrt(C)), b_qkv=bf16_randn((C,), 711, 0.1),
+             w_kv=bf16_randn((2 * C, C), 712, 1.0 / math.sqrt(C)), b_kv=bf16_randn((2 * C,), 713, 0.1),
+             w_o=bf16_randn((C, C), 714, 1.0 / math.sqrt(C)), b_o=bf16_randn((C,), 715, 0.1))
+    wd = pab.module_weights(**{k: v.to(DEV) for k, v in w.items()})
+    out = pab.pab_module_compute(2, x.to(DEV), text.to(DEV), wd, heads)
+    torch.cuda.synchronize()
+    want = mo.cross_attention_module(f64(x), f64(text), f64(w["w_qkv"]), f64(w["b_qkv"]), f64(w["w_kv"]), f64(w["b_kv"]),
+                                     f64(w["w_o"]), f64(w["b_o"]), heads)
+    check_module(out, want, "cross module")
+
+
+def test_module_broadcast_schedule_and_reuse(pab):
+    """Module-level PAB on a small video: computed steps match the oracle run on that step's
+    input, reused steps launch nothing and hand back the very bytes of the last computed step."""
+    from oracle import pab_oracle as orc
+    T, S, heads, D, n_steps, lo, hi = 4, 40, 4, 32, 8, 1, 6
+    C = heads * D
+    cfg = pab.make_config(2, T, S, 8, heads, D, pab.BF16, n_steps, (2, 3, 0), lo, hi)
+    ctx = pab.PabContext(cfg, DEV)
+    ctx.workspace.fill_(0xFF)
+    scratch = pab.module_scratch(T, S, 8, heads, D, DEV)
+    ws = [[self_weights(C, heads, 900 + 37 * (2 * b + k)) for k in range(2)] for b in range(2)]
+    wds = [[pab.module_weights(**{n: v.to(DEV) for n, v in w.items()}) for w in row] for row in ws]
+    last = {}
+    launches = 0
+    for step in range(n_steps):
+        for block in range(2):
+            for kind in range(2):
+                x = bf16_randn((T, S, C), 10000 + 100 * step + 10 * block + kind)
+                want_dec = orc.schedule(step, lo, hi, cfg.interval[kind])
+                if want_dec == 0:
+                    dec, ptr = ctx.pab_module_attention(block, kind, step, x.to(DEV), None, wds[block][kind], scratch)
+                    launches += 1
+                else:   # nothing may be read on a reused step: hand in nothing at all
+                    dec, ptr = ctx.pab_module_attention(block, kind, step, None, None, None, None)
+                torch.cuda.synchronize()
+                assert dec == want_dec, (step, block, kind)
+                assert ptr == ctx.pab_slot_ptr(block, kind)
+                got = ctx.slot_tensor(block, kind).reshape(T, S, C)
+                if dec == 0:
+                    check_module(got, oracle_self(kind, x, ws[block][kind], heads), "video step %d" % step)
+                    last[(block, kind)] = got.clone()
+                else:
+                    assert torch.equal(got, last[(block, kind)]), (step, block, kind)
+    assert ctx.pab_launch_count() == launches
+    ctx.pab_destroy()
+
+
+def test_module_argument_errors(pab):
+    T, S, heads, D = 2, 16, 4, 32
+    C = heads * D
+    x = torch.zeros((T, S, C), device=DEV, dtype=torch.bfloat16)
+    w = self_weights(C, heads, 1)
+    wd = pab.module_weights(**{k: v.to(DEV) for k, v in w.items()})
+    scratch = pab.module_scratch(T, S, 0, heads, D, DEV)
+    out = torch.empty_like(x)
+    import ctypes
+    f = pab.lib.pab_module_compute
+    ok = (0, T, S, 0, heads, D, x.data_ptr(), None, ctypes.byref(wd), scratch.data_ptr(), scratch.numel(), out.data_ptr(), None)
+    assert f(*ok) == pab.OK
+    bad = list(ok); bad[10] = scratch.numel() // 2
+    assert f(*bad) == pab.ENOMEM
+    bad = list(ok); bad[6] = None
+    assert f(*bad) == pab.EINVAL
+    bad = list(ok); bad[0] = 2            # cross without text
+    assert f(*bad) == pab.EINVAL
+    bad = list(ok); bad[4], bad[5] = 3, 72   # hidden size 216: not a multiple of 32
+    assert f(*bad) == pab.EINVAL
+    wd2 = pab.module_weights(**{k: v.to(DEV) for k, v in w.items() if k != "gamma_k"})
+    bad = list(ok); bad[8] = ctypes.byref(wd2)
+    assert f(*bad) == pab.EINVAL
+    torch.cuda.synchronize()
