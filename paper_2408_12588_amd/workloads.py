@@ -157,3 +157,46 @@ def sample_rows(wl: Workload, n: int, seed: int) -> np.ndarray:
     corners = np.array([[0, 0, 0], [wl.T - 1, wl.S - 1, wl.heads - 1],
                         [0, wl.S - 1, 0], [wl.T - 1, 0, wl.heads - 1]])
     return np.concatenate([corners, rows])[:max(n, 4)].astype(np.int64)
+
+
+# ---- module-level inputs (paper App. B.5 / B.6: the attention module around the operation) ----
+# Random-init stand-ins for trained weights: projection rows of about unit norm, modulation and
+# learned norm parameters small around their identity values.  Tensor ids 16.. keep these streams
+# apart from the q / k / v ones.
+_MODULE_TENSORS = ("shift", "scale", "w_qkv", "b_qkv", "gamma_q", "beta_q", "gamma_k", "beta_k", "w_kv", "b_kv",
+                   "w_o", "b_o")
+
+
+def make_module_weights(wl: Workload, block: int, kind: int) -> dict:
+    """bf16 CPU tensors of one attention module's weights, named as the library's weight struct.
+    Self attention (spatial, temporal): shift, scale, w_qkv [3C, C], b_qkv, gamma/beta of q and k, w_o, b_o.
+    Cross attention: w_qkv [C, C] (queries), b_qkv, w_kv [2C, C], b_kv, w_o, b_o."""
+    C, D = wl.heads * wl.head_dim, wl.head_dim
+    inv = 1.0 / np.sqrt(C)
+
+    def draw(name, shape, scale, offset=0.0):
+        a = normal(shape, wl.seed, block, kind, 0, 16 + _MODULE_TENSORS.index(name)) * np.float32(scale) + np.float32(offset)
+        return torch.from_numpy(a).to(torch.bfloat16)
+
+    w = {"w_o": draw("w_o", (C, C), inv), "b_o": draw("b_o", (C,), 0.1)}
+    if kind == CROSS:
+        w.update(w_qkv=draw("w_qkv", (C, C), inv), b_qkv=draw("b_qkv", (C,), 0.1),
+                 w_kv=draw("w_kv", (2 * C, C), inv), b_kv=draw("b_kv", (2 * C,), 0.1))
+    else:
+        w.update(shift=draw("shift", (C,), 0.3), scale=draw("scale", (C,), 0.3),
+                 w_qkv=draw("w_qkv", (3 * C, C), inv), b_qkv=draw("b_qkv", (3 * C,), 0.1),
+                 gamma_q=draw("gamma_q", (D,), 0.2, 1.0), beta_q=draw("beta_q", (D,), 0.2),
+                 gamma_k=draw("gamma_k", (D,), 0.2, 1.0), beta_k=draw("beta_k", (D,), 0.2))
+    return w
+
+
+def make_module_input(wl: Workload, block: int, kind: int, step: int) -> torch.Tensor:
+    """Hidden states x ``[T, S, C]`` (bf16, N(0,1)) entering the module of (block, kind) at a step."""
+    C = wl.heads * wl.head_dim
+    return torch.from_numpy(normal((wl.T, wl.S, C), wl.seed, block, kind, step, 8)).to(torch.bfloat16)
+
+
+def make_text(wl: Workload) -> torch.Tensor:
+    """Text tokens ``[L, C]`` (bf16, N(0,1)) the cross-attention modules attend to; one per workload."""
+    C = wl.heads * wl.head_dim
+    return torch.from_numpy(normal((max(wl.L, 1), C), wl.seed, 0xFFFD, 0xFD, 0, 9)).to(torch.bfloat16)

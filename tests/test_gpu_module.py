@@ -217,3 +217,35 @@ def test_module_argument_errors(pab):
     bad = list(ok); bad[8] = ctypes.byref(wd2)
     assert f(*bad) == pab.EINVAL
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["opensora_480p", "osp_512_long"])
+def test_module_full_size_sampled(pab, name):
+    """The benchmark's shapes and launch configuration.  The modules are independent per frame
+    (spatial), per position (temporal) and per token (cross), so the oracle can be run on a few
+    frames / positions / tokens of the full-size input and compared with those outputs."""
+    from paper_2408_12588_amd import workloads as W
+    wl = W.BY_NAME[name]
+    T, S, H = wl.T, wl.S, wl.heads
+    text = W.make_text(wl)
+    scratch = pab.module_scratch(T, S, wl.L, H, wl.head_dim, DEV)
+    for kind in range(3):
+        print("full-size module", name, W.KIND_NAMES[kind], flush=True)
+        x = W.make_module_input(wl, 1, kind, 2)
+        w = W.make_module_weights(wl, 1, kind)
+        wd = pab.module_weights(**{n: t.to(DEV) for n, t in w.items()})
+        out = pab.pab_module_compute(kind, x.to(DEV), text.to(DEV) if kind == 2 else None, wd, H, scratch=scratch)
+        torch.cuda.synchronize()
+        out = out.cpu()
+        assert torch.isfinite(out.float()).all()
+        if kind == 0:
+            for t in (0, T - 1):
+                check_module(out[t:t + 1], oracle_self(0, x[t:t + 1], w, H), "%s spatial frame %d" % (name, t))
+        elif kind == 1:
+            for s in (0, S // 3, S - 1):
+                check_module(out[:, s:s + 1], oracle_self(1, x[:, s:s + 1], w, H), "%s temporal position %d" % (name, s))
+        else:
+            for t, s0 in ((0, 0), (T - 1, S - 8), (T // 2, S // 2)):
+                want = mo.cross_attention_module(f64(x[t:t + 1, s0:s0 + 8]), f64(text), f64(w["w_qkv"]), f64(w["b_qkv"]),
+                                                 f64(w["w_kv"]), f64(w["b_kv"]), f64(w["w_o"]), f64(w["b_o"]), H)
+                check_module(out[t:t + 1, s0:s0 + 8], want, "%s cross tokens (%d, %d..)" % (name, t, s0))
