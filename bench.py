@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--workload", default="opensora_480p")
     ap.add_argument("--pool", type=int, default=8, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-module", action="store_true", help="skip the module-level section")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--kind-reps", type=int, default=40, help="launches per kind in the per-kind section")
     ap.add_argument("--profile-kind", default=None, choices=["spatial", "temporal", "cross"],
@@ -225,9 +226,97 @@ def main():
                 "effective_tflops": round(sum(flops0) / sec / 1e12, 3)},
         "kinds": kinds,
     }
+    if not args.no_module and wl.dtype == "bf16":
+        result["module"] = module_section(wl, pool, args, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     print(json.dumps(result), flush=True)
+
+
+def module_section(wl, pool, args, dev):
+    """The same video with the whole attention module as the broadcast object (paper App. B.5 / B.6):
+    layernorm + modulate, qkv projection, q/k layernorm (+ rotary), attention, output projection per
+    computed call; reuse still costs nothing.  One weight set per (block, kind), random init."""
+    import math
+    import torch
+    from paper_2408_12588_amd import pab, workloads as W
+    T, S, H, D = wl.T, wl.S, wl.heads, wl.head_dim
+    C, L, tok = H * D, max(wl.L, 1), wl.T * wl.S
+    stream = torch.cuda.current_stream()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed + 1)
+
+    def rn(shape, scale=1.0, offset=0.0):
+        return (torch.randn(shape, generator=gen, device=dev) * scale + offset).to(torch.bfloat16)
+
+    def weights(kind):
+        if kind == W.CROSS:
+            return pab.module_weights(w_qkv=rn((C, C), 1 / math.sqrt(C)), b_qkv=rn((C,), 0.1),
+                                      w_kv=rn((2 * C, C), 1 / math.sqrt(C)), b_kv=rn((2 * C,), 0.1),
+                                      w_o=rn((C, C), 1 / math.sqrt(C)), b_o=rn((C,), 0.1))
+        return pab.module_weights(shift=rn((C,), 0.3), scale=rn((C,), 0.3), w_qkv=rn((3 * C, C), 1 / math.sqrt(C)),
+                                  b_qkv=rn((3 * C,), 0.1), gamma_q=rn((D,), 0.2, 1.0), beta_q=rn((D,), 0.2),
+                                  gamma_k=rn((D,), 0.2, 1.0), beta_k=rn((D,), 0.2),
+                                  w_o=rn((C, C), 1 / math.sqrt(C)), b_o=rn((C,), 0.1))
+
+    calls = wl.calls_per_step()
+    wts = {(b, k): weights(k) for b, k in calls}
+    text = rn((L, C))
+    scratch = pab.module_scratch(T, S, wl.L, H, D, dev)
+    xs = [p[0].view(T, S, C) for p in pool]
+
+    def module_flops(kind):
+        if kind == W.CROSS:
+            return wl.flops(kind) + 2.0 * tok * C * C * 2 + 2.0 * L * C * 2 * C
+        return wl.flops(kind) + 2.0 * tok * C * 3 * C + 2.0 * tok * C * C
+
+    def video(intervals):
+        ctx = pab.PabContext(pab.config_of(wl, intervals), dev)
+        flops, launches = 0.0, [0, 0, 0]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        i = 0
+        for step in range(wl.n_steps):
+            for block, kind in calls:
+                dec, _ = ctx.pab_module_attention(block, kind, step, xs[i % len(xs)], text if kind == W.CROSS else None,
+                                                  wts[(block, kind)], scratch)
+                i += 1
+                if dec == pab.COMPUTE:
+                    flops += module_flops(kind)
+                    launches[kind] += 1
+        torch.cuda.synchronize()
+        sec = time.perf_counter() - t0
+        ctx.pab_destroy()
+        return sec, flops, launches
+
+    video(None)                                   # warm-up: one video under the PAB schedule
+    sec, flops, launches = video(None)
+    sec0, flops0, launches0 = video((1, 1, 1))
+    per_kind = {}
+    out = torch.empty((T, S, C), device=dev, dtype=torch.bfloat16)
+    for kind in (W.SPATIAL, W.TEMPORAL, W.CROSS):
+        if wl.intervals[kind] == 0:
+            continue
+        blocks = [b for b, k in calls if k == kind]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(8, args.kind_reps // 2)
+        for timed in (False, True):
+            if timed:
+                e0.record(stream)
+            for i in range(reps if timed else 2):
+                pab.pab_module_compute(kind, xs[i % len(xs)], text if kind == W.CROSS else None,
+                                       wts[(blocks[i % len(blocks)], kind)], H, scratch=scratch, out=out)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        per_kind[W.KIND_NAMES[kind]] = {"ms_per_call": round(ms, 4),
+                                        "tflops": round(module_flops(kind) / (ms * 1e-3) / 1e12, 2)}
+    return {"object": "output of the attention module (layernorm+modulate, qkv proj, q/k layernorm, rotary, attention, o proj)",
+            "value": round(flops / sec / 1e12, 3), "unit": "TFLOP/s",
+            "latency_ms": {"pab": round(sec * 1e3, 3), "no_pab": round(sec0 * 1e3, 3), "steps": wl.n_steps},
+            "time_reduction": round(1.0 - sec / sec0, 4),
+            "skipped_flop_fraction": round(1.0 - flops / flops0, 4),
+            "launches_pab": launches, "launches_no_pab": launches0, "kinds": per_kind}
 
 
 def cpu_baseline(wl, target_seconds):
