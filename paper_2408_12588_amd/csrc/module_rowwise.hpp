@@ -9,10 +9,10 @@
 //   qk_norm_rope_kernel: in place on the projected q and k, LayerNorm over the
 //                        head dimension D with a learned scale and shift, then
 //                        (temporal attention only) the rotary position
-//                        embedding by frame index.  One lane per (token, head)
-//                        row; the rows of a wavefront are loaded and stored
-//                        as whole 16-byte chunks in memory order and transposed
-//                        through LDS.
+//                        embedding by frame index.  A few lanes per (token,
+//                        head) row, so that a wavefront reads and writes one
+//                        contiguous stretch of memory and a row fits in a
+//                        handful of registers.
 #pragma once
 #include "mfma_util.hpp"
 
@@ -90,80 +90,79 @@ struct QkNormParams {
   float log2_base;                 // log2 of the rotary base
 };
 
-// One wavefront = 64 consecutive (token, head) rows of q or of k (blockIdx.y picks which).
-template <int D>
+// LPR lanes share one (token, head) row, D / LPR consecutive elements each (a multiple of 8 and
+// of 2); a wavefront covers 64 / LPR consecutive rows of q or of k (blockIdx.y picks which), i.e.
+// one contiguous stretch of memory that its lanes read and write in order.  The two row sums are
+// combined across the lanes of a row by lane permutes.
+template <int D, int LPR>
 __global__ __launch_bounds__(256) void qk_norm_rope_kernel(const QkNormParams p) {
-  constexpr int CH = D / 8;                 // chunks per row
-  __shared__ __attribute__((aligned(16))) bf16_t smem[4][64 * D];
+  constexpr int EPL = D / LPR;              // elements per lane
+  constexpr int CPL = EPL / 8;              // 16-byte chunks per lane
+  constexpr int RPW = 64 / LPR;             // rows per wavefront
+  static_assert(D % LPR == 0 && EPL % 8 == 0, "a lane holds whole chunks");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  bf16_t *buf = smem[wave];
   bf16_t *base = blockIdx.y == 0 ? p.q : p.k;
   const bf16_t *gamma = blockIdx.y == 0 ? p.gq : p.gk, *beta = blockIdx.y == 0 ? p.bq : p.bk;
   const long long n_rows = (long long)p.n_tok * p.H;
-  const long long row0 = ((long long)blockIdx.x * 4 + wave) * 64;
-  if (row0 >= n_rows) return;
-  const int rows = (int)(n_rows - row0 < 64 ? n_rows - row0 : 64);
-  bf16_t *g0 = base + row0 * D;   // the rows of q (or k) are dense: 64 rows = 64 * D contiguous elements
+  const int r_in_wave = lane / LPR, part = lane % LPR;
+  const long long row = ((long long)blockIdx.x * 4 + wave) * RPW + r_in_wave;
+  const bool live = r_in_wave < RPW && row < n_rows;
+  bf16_t *g0 = base + row * D + part * EPL;
 
-  // memory order -> LDS (same order), whole chunks, consecutive lanes on consecutive chunks
+  float v[EPL];
+  float s = 0.0f;
 #pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const int c = lane + 64 * i;
-    if (c < rows * CH) *reinterpret_cast<bf16x8 *>(buf + 8 * c) = *reinterpret_cast<const bf16x8 *>(g0 + 8 * c);
-  }
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-
-  if (lane < rows) {
-    float v[D];
+  for (int i = 0; i < CPL; ++i) {
+    bf16x8 t = zero8();
+    if (live) t = *reinterpret_cast<const bf16x8 *>(g0 + 8 * i);
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const bf16x8 t = *reinterpret_cast<const bf16x8 *>(buf + lane * D + 8 * i);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[8 * i + e] = (float)t[e];
-    }
-    float s = 0.0f;
-#pragma unroll
-    for (int e = 0; e < D; ++e) s += v[e];
-    const float mean = s / (float)D;
-    float ss = 0.0f;
-#pragma unroll
-    for (int e = 0; e < D; ++e) {
-      const float d = v[e] - mean;
-      ss += d * d;
-    }
-    const float rstd = 1.0f / sqrtf(ss / (float)D + p.eps);
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const bf16x8 gm = *reinterpret_cast<const bf16x8 *>(gamma + 8 * i);
-      const bf16x8 bt = *reinterpret_cast<const bf16x8 *>(beta + 8 * i);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[8 * i + e] = (v[8 * i + e] - mean) * rstd * (float)gm[e] + (float)bt[e];
-    }
-    if (p.rope) {
-      const float pos = (float)(int)((row0 + lane) / p.H / p.S);   // frame index of this row's token
-#pragma unroll
-      for (int i = 0; i < D / 2; ++i) {
-        const float theta = __builtin_amdgcn_exp2f(-(2.0f * i / (float)D) * p.log2_base);
-        float sn, cs;
-        sincosf(pos * theta, &sn, &cs);
-        const float a = v[2 * i], b = v[2 * i + 1];
-        v[2 * i] = a * cs - b * sn;
-        v[2 * i + 1] = a * sn + b * cs;
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      bf16x8 o;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[8 * i + e];
-      *reinterpret_cast<bf16x8 *>(buf + lane * D + 8 * i) = o;
+    for (int e = 0; e < 8; ++e) {
+      v[8 * i + e] = (float)t[e];
+      s += v[8 * i + e];
     }
   }
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  const int first = lane - part;            // first lane of this row
+  float tot = 0.0f;
 #pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const int c = lane + 64 * i;
-    if (c < rows * CH) *reinterpret_cast<bf16x8 *>(g0 + 8 * c) = *reinterpret_cast<const bf16x8 *>(buf + 8 * c);
+  for (int l = 0; l < LPR; ++l) tot += __shfl(s, first + l);
+  const float mean = tot / (float)D;
+  float ss = 0.0f;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    const float d = v[e] - mean;
+    ss += d * d;
+  }
+  tot = 0.0f;
+#pragma unroll
+  for (int l = 0; l < LPR; ++l) tot += __shfl(ss, first + l);
+  const float rstd = 1.0f / sqrtf(tot / (float)D + p.eps);
+  if (!live) return;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    const bf16x8 gm = *reinterpret_cast<const bf16x8 *>(gamma + part * EPL + 8 * i);
+    const bf16x8 bt = *reinterpret_cast<const bf16x8 *>(beta + part * EPL + 8 * i);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[8 * i + e] = (v[8 * i + e] - mean) * rstd * (float)gm[e] + (float)bt[e];
+  }
+  if (p.rope) {
+    const float pos = (float)(int)(row / p.H / p.S);   // frame index of this row's token
+#pragma unroll
+    for (int i = 0; i < EPL / 2; ++i) {
+      const float pair = (float)(part * (EPL / 2) + i);          // index of the feature pair inside the head
+      const float theta = __builtin_amdgcn_exp2f(-(2.0f * pair / (float)D) * p.log2_base);
+      float sn, cs;
+      sincosf(pos * theta, &sn, &cs);
+      const float a = v[2 * i], b = v[2 * i + 1];
+      v[2 * i] = a * cs - b * sn;
+      v[2 * i + 1] = a * sn + b * cs;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[8 * i + e];
+    *reinterpret_cast<bf16x8 *>(g0 + 8 * i) = o;
   }
 }
 

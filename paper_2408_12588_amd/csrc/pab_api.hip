@@ -318,10 +318,12 @@ int launch_qk_norm(int n_tok, int H, int D, int S, int rope, void *q, void *k, c
   p.gk = static_cast<const pab::bf16_t *>(w->gamma_k); p.bk = static_cast<const pab::bf16_t *>(w->beta_k);
   p.n_tok = n_tok; p.H = H; p.S = S; p.rope = rope; p.eps = 1e-6f;
   p.log2_base = 13.287712379549449f;   // log2(10000)
-  const long long waves = ((long long)n_tok * H + 63) / 64;
+  // three lanes per 72-element row (21 rows per wavefront), two per 32-element row (32 rows)
+  const int rows_per_wave = D == 72 ? 21 : 32;
+  const long long waves = ((long long)n_tok * H + rows_per_wave - 1) / rows_per_wave;
   const dim3 grid((unsigned)((waves + 3) / 4), 2), block(256);
-  if (D == 72) hipLaunchKernelGGL((pab::qk_norm_rope_kernel<72>), grid, block, 0, st, p);
-  else hipLaunchKernelGGL((pab::qk_norm_rope_kernel<32>), grid, block, 0, st, p);
+  if (D == 72) hipLaunchKernelGGL((pab::qk_norm_rope_kernel<72, 3>), grid, block, 0, st, p);
+  else hipLaunchKernelGGL((pab::qk_norm_rope_kernel<32, 2>), grid, block, 0, st, p);
   return PAB_OK;
 }
 
