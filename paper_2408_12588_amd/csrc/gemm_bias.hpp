@@ -6,12 +6,11 @@
 // with the weight rows as the A operand and the token rows as the B operand a
 // 32x32 tile is C^T[n, m], every lane owns one token and 16 of its outputs.
 //
-// One workgroup = 4 wavefronts (2 x 2) computes a 128-token x 256-feature tile,
-// each wavefront 64 x 128 (2 x 4 MFMA tiles, 128 accumulator registers).  The
-// K dimension streams through a ring of NST LDS stages of 32 columns: 128 token
-// rows and 256 weight rows of 64 bytes each per stage, copied global -> LDS
-// directly (16 bytes per lane) two stages ahead of their use, one barrier per
-// stage.  Rows are 64 bytes, so row r's four 16-byte chunks are stored at
+// One workgroup of WM x WN wavefronts computes a BM-token x BN-feature tile,
+// each wavefront TM x TN MFMA tiles of it.  The K dimension streams through a
+// ring of NST LDS stages of 32 columns: BM token rows and BN weight rows of 64
+// bytes each per stage, copied global -> LDS directly (16 bytes per lane)
+// NST-1 stages ahead of their use, one barrier per stage.  Rows are 64 bytes, so row r's four 16-byte chunks are stored at
 // position q ^ ((r >> 2) & 3): the 16 lanes that read one chunk column of 16
 // consecutive rows then hit 16 different bank groups.
 //
@@ -36,22 +35,27 @@ struct GemmParams {
   int n_mt, n_nt;       // token / feature tiles
 };
 
-template <int NST>
-__global__ __launch_bounds__(256, 2) void gemm_bias_kernel(const GemmParams p) {
-  constexpr int BM = 128, BN = 256, BK = 32;
+// NST: ring depth.  WM x WN wavefronts per workgroup, each computing TM x TN MFMA tiles of 32 x 32
+// (tokens x features): the workgroup tile is BM = 32 WM TM tokens by BN = 32 WN TN features.
+template <int NST, int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bias_kernel(const GemmParams p) {
+  constexpr int NW = WM * WN;
+  constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN, BK = 32;
   constexpr int ROWS = BM + BN;                 // rows per stage: token rows, then weight rows
-  constexpr int STAGE_ELEMS = ROWS * BK;        // 24 KB
-  constexpr int ROUNDS = ROWS * 4 / 64;         // 64-chunk copy rounds per stage = 24
-  constexpr int MYR = ROUNDS / 4;               // per wavefront = 6: two of token rows, four of weight rows
+  constexpr int STAGE_ELEMS = ROWS * BK;
+  constexpr int ROUNDS = ROWS * 4 / 64;         // 64-chunk copy rounds per stage (16 rows each)
+  constexpr int MYR = ROUNDS / NW;              // per wavefront
+  constexpr int MYR_TOK = BM / 16 / NW;         // ... of which token rows (round r = wave + NW i: i < MYR_TOK)
   constexpr int GM = 4;                         // token tiles an XCD keeps in flight together
   static_assert(NST >= 3 && (NST - 2) * MYR < 16, "ring depth / vmcnt immediates");
+  static_assert(ROUNDS % NW == 0 && (BM / 16) % NW == 0, "copy rounds must deal evenly to the wavefronts");
 
   __shared__ __attribute__((aligned(16))) bf16_t smem[NST * STAGE_ELEMS];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j = lane & 31, g = lane >> 5;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
 
   // ---- which tile ----
@@ -70,19 +74,19 @@ __global__ __launch_bounds__(256, 2) void gemm_bias_kernel(const GemmParams p) {
   unsigned voff[MYR];
 #pragma unroll
   for (int i = 0; i < MYR; ++i) {
-    const int r = wave + 4 * i;
+    const int r = wave + NW * i;
     const int row = 16 * r + (lane >> 2);
     const int q = (lane & 3) ^ ((row >> 2) & 3);
     long long grow;
-    if (i < 2) grow = min(m0 + row, M - 1);          // token rows (rounds 0..7)
-    else grow = min(n0 + row - BM, N - 1);           // weight rows (rounds 8..23)
+    if (i < MYR_TOK) grow = min(m0 + row, M - 1);    // token rows
+    else grow = min(n0 + row - BM, N - 1);           // weight rows
     voff[i] = (unsigned)(2 * (grow * K + 8 * q));
   }
   auto issue = [&](int kt, int stage) {
 #pragma unroll
     for (int i = 0; i < MYR; ++i) {
-      const int r = wave + 4 * i;
-      dma16_to_lds((i < 2 ? p.A : p.W) + (long long)kt * BK, voff[i], smem_addr + 2 * stage * STAGE_ELEMS + 1024 * r);
+      const int r = wave + NW * i;
+      dma16_to_lds((i < MYR_TOK ? p.A : p.W) + (long long)kt * BK, voff[i], smem_addr + 2 * stage * STAGE_ELEMS + 1024 * r);
     }
   };
   auto wait_staged = [&](int stages) {   // at most `stages` of this wavefront's staged K slices still in flight
@@ -95,20 +99,20 @@ __global__ __launch_bounds__(256, 2) void gemm_bias_kernel(const GemmParams p) {
   const int npre = nk < NST - 1 ? nk : NST - 1;
   for (int kt = 0; kt < npre; ++kt) issue(kt, kt);
 
-  f32x16 acc[2][4];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < TM; ++a)
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < TN; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
   // fragment addresses inside a stage (elements): row * 32 + 8 * (chunk ^ swizzle(row))
-  int tok_row[2], w_row[4];
+  int tok_row[TM], w_row[TN];
 #pragma unroll
-  for (int a = 0; a < 2; ++a) tok_row[a] = wm * 64 + a * 32 + j;
+  for (int a = 0; a < TM; ++a) tok_row[a] = (wm * TM + a) * 32 + j;
 #pragma unroll
-  for (int b = 0; b < 4; ++b) w_row[b] = BM + wn * 128 + b * 32 + j;
+  for (int b = 0; b < TN; ++b) w_row[b] = BM + (wn * TN + b) * 32 + j;
 
   for (int kt = 0; kt < nk; ++kt) {
     const int ahead = nk - 1 - kt;                     // staged slices beyond kt
@@ -119,45 +123,70 @@ __global__ __launch_bounds__(256, 2) void gemm_bias_kernel(const GemmParams p) {
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       const int q = 2 * ks + g;
-      bf16x8 tf[2], wf[4];
+      bf16x8 tf[TM], wf[TN];
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < TM; ++a)
         tf[a] = *reinterpret_cast<const bf16x8 *>(st + tok_row[a] * BK + 8 * (q ^ ((tok_row[a] >> 2) & 3)));
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
+      for (int b = 0; b < TN; ++b)
         wf[b] = *reinterpret_cast<const bf16x8 *>(st + w_row[b] * BK + 8 * (q ^ ((w_row[b] >> 2) & 3)));
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = mfma32(wf[b], tf[a], acc[a][b]);
+        for (int b = 0; b < TN; ++b) acc[a][b] = mfma32(wf[b], tf[a], acc[a][b]);
     }
   }
 
-  // ---- epilogue: lane (j, g) holds, for token m0 + wm*64 + a*32 + j, features
-  //      n0 + wn*128 + b*32 + 8 rq + 4 g + 0..3 in registers 4 rq .. 4 rq + 3 ----
+  // ---- epilogue: lane (j, g) holds, for token (wm TM + a) 32 + j of the tile, features
+  //      (wn TN + b) 32 + 8 rq + 4 g + 0..3 in registers 4 rq .. 4 rq + 3.  Written like that, a store
+  //      instruction would scatter 16-byte pieces over 32 rows; instead each wavefront passes its
+  //      32 TM x 32 TN block through LDS (the ring is free now) and writes whole row segments. ----
+  constexpr int WT = 32 * TN;                   // features of a wavefront's block
+  constexpr int PITCH = WT + 8;                 // LDS row pitch (elements): rows 16 bytes apart in bank phase
+  constexpr int CHR = WT / 8;                   // 16-byte chunks per row segment
+  static_assert(NW * 32 * PITCH <= NST * STAGE_ELEMS, "output staging must fit the ring");
+  __syncthreads();                              // everyone is done reading the last K slice
+  bf16_t *stg = smem + wave * (32 * PITCH);     // one 32-token block at a time
   bf16_t *C = reinterpret_cast<bf16_t *>(p.C);
+  const int nw0 = n0 + wn * WT;                 // first feature of the wavefront's block
 #pragma unroll
-  for (int b = 0; b < 4; ++b)
+  for (int a = 0; a < TM; ++a) {
 #pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
-      const int n = n0 + wn * 128 + b * 32 + 8 * rq + 4 * g;
-      if (n >= N) continue;
-      const int plane = n / p.n_split;
-      bf16_t *Cn = C + plane * p.plane_stride + (n - plane * p.n_split);
-      float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (p.bias) {
-        const bf16x4 b4 = *reinterpret_cast<const bf16x4 *>(p.bias + n);
+    for (int b = 0; b < TN; ++b)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) bv[e] = (float)b4[e];
+      for (int rq = 0; rq < 4; ++rq) {
+        const int nl = b * 32 + 8 * rq + 4 * g;   // feature inside the block
+        float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (p.bias && nw0 + nl < N) {
+          const bf16x4 b4 = *reinterpret_cast<const bf16x4 *>(p.bias + nw0 + nl);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[e] = (float)b4[e];
+        }
+        Io<bf16_t>::store4(stg + j * PITCH + nl, acc[a][b][4 * rq] + bv[0], acc[a][b][4 * rq + 1] + bv[1],
+                           acc[a][b][4 * rq + 2] + bv[2], acc[a][b][4 * rq + 3] + bv[3]);
       }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    // 32 rows x CHR chunks, consecutive lanes on consecutive chunks of a row
+    const int mrow0 = m0 + (wm * TM + a) * 32;
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        const int m = m0 + wm * 64 + a * 32 + j;
-        if (m < M)
-          Io<bf16_t>::store4(Cn + (long long)m * p.ldc, acc[a][b][4 * rq] + bv[0], acc[a][b][4 * rq + 1] + bv[1],
-                             acc[a][b][4 * rq + 2] + bv[2], acc[a][b][4 * rq + 3] + bv[3]);
+    for (int i = 0; i < (32 * CHR + 63) / 64; ++i) {
+      const int c = lane + 64 * i, r = c / CHR, ch = c % CHR;
+      const int n = nw0 + 8 * ch;
+      if (c < 32 * CHR && mrow0 + r < M && n < N) {
+        const bf16x8 val = *reinterpret_cast<const bf16x8 *>(stg + r * PITCH + 8 * ch);
+        const int plane = n / p.n_split;
+        bf16_t *dst = C + plane * p.plane_stride + (long long)(mrow0 + r) * p.ldc + (n - plane * p.n_split);
+        if (n + 8 <= N) {
+          *reinterpret_cast<bf16x8 *>(dst) = val;
+        } else {   // N is a multiple of 4: the last chunk of a row may be half
+          bf16x4 half;
+          half[0] = val[0]; half[1] = val[1]; half[2] = val[2]; half[3] = val[3];
+          *reinterpret_cast<bf16x4 *>(dst) = half;
+        }
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  }
 }
 
 }  // namespace pab

@@ -261,6 +261,10 @@ size_t module_plane_bytes(int T, int S, int L, int H, int D) {
   return ((size_t)rows * H * D * 2 + 255) / 256 * 256;
 }
 
+// projection kernel shape: 2 x 2 wavefronts of 2 x 4 MFMA tiles = 128 tokens x 256 features per workgroup
+constexpr int GEMM_NST = 3, GEMM_WM = 2, GEMM_WN = 2, GEMM_TM = 2, GEMM_TN = 4;
+constexpr int GEMM_BM = 32 * GEMM_WM * GEMM_TM, GEMM_BN = 32 * GEMM_WN * GEMM_TN;
+
 int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
                 int n_split, long long plane_stride, hipStream_t st) {
   if (!A || !W || !C) return fail(PAB_EINVAL, "A, W and C must not be NULL");
@@ -269,7 +273,7 @@ int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *b
     return fail(PAB_EINVAL, "A, W, bias and C must be 16-byte aligned");
   if (M < 1 || N < 1) return fail(PAB_EINVAL, "M=%d N=%d must be >= 1", M, N);
   if (K < 32 || K % 32) return fail(PAB_EINVAL, "K=%d must be a positive multiple of 32", K);
-  if (N % 4 || ldc % 4 || n_split % 4 || plane_stride % 4)
+  if (N % 4 || ldc % 4 || plane_stride % 4 || (n_split != N && n_split % 8))
     return fail(PAB_EINVAL, "N=%d and ldc=%lld must be multiples of 4", N, ldc);
   if ((long long)M * K > 0x7fffffffLL || (long long)N * K > 0x7fffffffLL)
     return fail(PAB_EINVAL, "matrix too large");
@@ -280,13 +284,14 @@ int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *b
   p.C = C;
   p.M = M; p.N = N; p.K = K; p.ldc = ldc;
   p.n_split = n_split; p.plane_stride = plane_stride;
-  p.n_mt = (M + 127) / 128;
-  p.n_nt = (N + 255) / 256;
+  p.n_mt = (M + GEMM_BM - 1) / GEMM_BM;
+  p.n_nt = (N + GEMM_BN - 1) / GEMM_BN;
   // an XCD owns every eighth token tile and takes them four at a time over all feature tiles
   const long long owned = (p.n_mt + 7) / 8, groups = (owned + 3) / 4;
   const long long grid = 8 * groups * 4 * p.n_nt;
   if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "matrix too large");
-  hipLaunchKernelGGL((pab::gemm_bias_kernel<3>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  hipLaunchKernelGGL((pab::gemm_bias_kernel<GEMM_NST, GEMM_WM, GEMM_WN, GEMM_TM, GEMM_TN>), dim3((unsigned)grid),
+                     dim3(64 * GEMM_WM * GEMM_WN), 0, st, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
   return PAB_OK;
