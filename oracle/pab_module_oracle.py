@@ -10,8 +10,8 @@ definition in NumPy fp64, one step per part, in the order of the workflow.  Only
 and bench.py's cpu_baseline leg may import this file; it shares nothing with the HIP path.
 
 parity unpinned: which normalisation "layernorm2" is, the rotary pairing and base of "pos emb",
-and the absence of a norm in the cross module are readings; the arithmetic of every part is
-pinned by tests/test_oracle_module.py.
+the absence of a norm in the cross module and the activation of the MLP are readings; the
+arithmetic of every part is pinned by tests/test_oracle_module.py.
 """
 from __future__ import annotations
 
@@ -100,3 +100,17 @@ def cross_attention_module(x, y, w_q, b_q, w_kv, b_kv, w_o, b_o, heads: int, n_t
     o = _attn.kind_attention(2, np.ascontiguousarray(q), np.ascontiguousarray(kv[:, 0]),
                              np.ascontiguousarray(kv[:, 1]), n_threads=n_threads)
     return linear(np.asarray(o, np.float64).reshape(T, S, C), w_o, b_o)
+
+
+def gelu_tanh(x: np.ndarray) -> np.ndarray:
+    """Activation of the MLP: GELU in its tanh form, 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))."""
+    x = np.asarray(x, np.float64)
+    return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
+
+
+def mlp_module(x, shift, scale, w1, b1, w2, b2) -> np.ndarray:
+    """The MLP module of a transformer block, the other object the paper broadcasts (Sec. 2.3 last
+    sentence, App. A.2.1 MLP table): layernorm + modulate as in the attention modules, a projection
+    to the inner width, the activation, a projection back.  x: [..., C]; w1: [F, C]; w2: [C, F]."""
+    h = modulate(layer_norm(x), shift, scale)
+    return linear(gelu_tanh(linear(h, w1, b1)), w2, b2)

@@ -108,6 +108,35 @@ long pab_oracle_window(const double *timesteps, long n_steps, double t_start,
 }
 
 /*
+ * Broadcast schedule of the MLP modules (App. A.2.1, table of MLP broadcast
+ * configurations; App. A.2.3 for the reason): the output computed at each of a
+ * few listed starting steps is retained and handed to the following steps of
+ * its broadcast range n, i.e. to the n-1 steps after the starting step; only
+ * blocks block_lo..block_hi take part.  Everything else is computed.
+ * `starts` are step indices (0-based, denoising order).  Written as the
+ * definition: look at every start in turn.
+ * Returns ORACLE_COMPUTE / ORACLE_REUSE and, through *src (may be NULL), the
+ * step whose output is delivered; ORACLE_BAD on meaningless arguments.
+ */
+int pab_oracle_mlp_schedule(long step, long block, const long *starts, long n_starts,
+                            long n, long block_lo, long block_hi, long *src)
+{
+    long i;
+    if (step < 0 || block < 0 || n < 1 || n_starts < 0 || (n_starts > 0 && !starts))
+        return ORACLE_BAD;
+    if (src) *src = step;
+    if (block < block_lo || block > block_hi) return ORACLE_COMPUTE;
+    for (i = 0; i < n_starts; ++i) {
+        if (starts[i] < 0) return ORACLE_BAD;
+        if (step > starts[i] && step <= starts[i] + (n - 1)) {
+            if (src) *src = starts[i];
+            return ORACLE_REUSE;
+        }
+    }
+    return ORACLE_COMPUTE;
+}
+
+/*
  * softmax(Q K^T / sqrt(D)) V for n_batch x n_head independent problems.
  *
  * q, o: sq query rows; k, v: sk key rows; each row has d contiguous fp64

@@ -58,6 +58,9 @@ def _load():
         lib.pab_oracle_schedule.argtypes = [ctypes.c_long] * 4
         lib.pab_oracle_source_step.restype = ctypes.c_long
         lib.pab_oracle_source_step.argtypes = [ctypes.c_long] * 4
+        lib.pab_oracle_mlp_schedule.restype = ctypes.c_int
+        lib.pab_oracle_mlp_schedule.argtypes = [ctypes.c_long, ctypes.c_long, ctypes.POINTER(ctypes.c_long), ctypes.c_long,
+                                                ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.POINTER(ctypes.c_long)]
         lib.pab_oracle_window.restype = ctypes.c_long
         lib.pab_oracle_window.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_long, ctypes.c_double,
                                           ctypes.c_double, ctypes.POINTER(ctypes.c_long), ctypes.POINTER(ctypes.c_long)]
@@ -92,6 +95,30 @@ def source_step(step: int, lo: int, hi: int, n: int) -> int:
 def schedule_row(n_steps: int, lo: int, hi: int, n: int) -> str:
     """One character per step: 'C' computed, 'R' reused."""
     return "".join("CR"[schedule(s, lo, hi, n)] for s in range(n_steps))
+
+
+def mlp_schedule(step: int, block: int, starts, n: int, block_lo: int, block_hi: int):
+    """(decision, source step) of the MLP broadcast (paper App. A.2.1, MLP table): 0 computed, 1 reused."""
+    arr = (ctypes.c_long * max(len(starts), 1))(*starts)
+    src = ctypes.c_long(-1)
+    r = _load().pab_oracle_mlp_schedule(step, block, arr, len(starts), n, block_lo, block_hi, ctypes.byref(src))
+    if r < 0:
+        raise ValueError("bad MLP schedule arguments")
+    return r, src.value
+
+
+def start_steps_from_timesteps(timesteps, start_timesteps):
+    """Step index of each starting timestep of the MLP table on a sampler's timestep list (never
+    increasing): the first step whose timestep is not above it.  None for a start below every timestep."""
+    out = []
+    for t0 in start_timesteps:
+        hit = None
+        for s, t in enumerate(timesteps):
+            if t <= t0:
+                hit = s
+                break
+        out.append(hit)
+    return out
 
 
 def window_from_timesteps(timesteps, t_start: float, t_end: float):

@@ -212,3 +212,63 @@ def test_cross_module_against_library_and_special_case():
     v_all = mo.linear(y, w_kv[C:], b_kv[C:])
     want0 = mo.linear(np.broadcast_to(v_all.mean(0), (T, S, C)), w_o, b_o)
     assert np.abs(got0 - want0).max() < 1e-10
+
+
+# ---- MLP module (Sec. 2.3 last sentence; App. A.2.1 MLP table) --------------------------------
+def test_gelu_tanh_matches_library_and_closed_forms():
+    x = np.linspace(-6.0, 6.0, 241)
+    assert np.abs(mo.gelu_tanh(x) - F.gelu(t64(x), approximate="tanh").numpy()).max() < 1e-14
+    assert mo.gelu_tanh(np.array([0.0]))[0] == 0.0
+    assert np.abs(mo.gelu_tanh(x) - mo.gelu_tanh(-x) - x).max() < 1e-12      # the even part cancels: g(x) - g(-x) = x
+    assert abs(mo.gelu_tanh(np.array([10.0]))[0] - 10.0) < 1e-12
+    assert abs(mo.gelu_tanh(np.array([1.0]))[0] - 0.5 * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * 1.044715))) < 1e-15
+    # the exact (erf) form differs visibly: the reading is the tanh form
+    assert abs(mo.gelu_tanh(np.array([2.0]))[0] - F.gelu(torch.tensor([2.0], dtype=torch.float64)).item()) > 5e-5
+
+
+def test_mlp_module_against_library_and_special_case():
+    C, Fw = 24, 96
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((3, 5, C))
+    shift, scale = 0.3 * rng.standard_normal(C), 0.3 * rng.standard_normal(C)
+    w1, b1 = rng.standard_normal((Fw, C)) / math.sqrt(C), 0.1 * rng.standard_normal(Fw)
+    w2, b2 = rng.standard_normal((C, Fw)) / math.sqrt(Fw), 0.1 * rng.standard_normal(C)
+    got = mo.mlp_module(x, shift, scale, w1, b1, w2, b2)
+    h = F.layer_norm(t64(x), (C,), eps=mo.EPS) * (1.0 + t64(scale)) + t64(shift)
+    want = F.linear(F.gelu(F.linear(h, t64(w1), t64(b1)), approximate="tanh"), t64(w2), t64(b2)).numpy()
+    assert np.abs(got - want).max() < 1e-12
+    # no signal through the first projection: every token gets W2 gelu(b1) + b2
+    got0 = mo.mlp_module(x, shift, scale, np.zeros_like(w1), b1, w2, b2)
+    assert np.abs(got0 - (w2 @ mo.gelu_tanh(b1) + b2)).max() < 1e-12
+
+
+def test_mlp_schedule_golden_and_invariants():
+    from oracle import pab_oracle as orc
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "timestep_windows.txt")) as f:
+        for line in f:
+            if line.startswith("mlp "):
+                head, steps, pattern = line[4:].split("|")
+                h = head.split()
+                rows.append((h[0], int(h[1]), int(h[2]), int(h[3]), int(h[4]), int(h[5]), int(h[6]),
+                             [int(v) for v in h[7:]], [int(v) for v in steps.split()], pattern.strip()))
+    assert len(rows) == 2
+    for name, first, stride, n_steps, n, blo, bhi, t_starts, want_steps, pattern in rows:
+        ts = [first - s * stride for s in range(n_steps)]
+        starts = orc.start_steps_from_timesteps(ts, t_starts)
+        assert starts == want_steps, name
+        assert len(pattern) == n_steps, name
+        got = "".join("CR"[orc.mlp_schedule(s, blo, starts, n, blo, bhi)[0]] for s in range(n_steps))
+        assert got == pattern, name
+        assert all(orc.mlp_schedule(s, bhi + 1, starts, n, blo, bhi) == (0, s) for s in range(n_steps)), name
+        for s in range(n_steps):
+            dec, src = orc.mlp_schedule(s, bhi, starts, n, blo, bhi)
+            if dec == 1:   # the source is a listed start, computed itself, at most n-1 steps back
+                assert src in starts and 0 < s - src <= n - 1
+                assert orc.mlp_schedule(src, bhi, starts, n, blo, bhi) == (0, src)
+    # range 1 never reuses; range 3 reuses two steps; text construction for a single start
+    for n in (1, 2, 3, 5):
+        row = "".join("CR"[orc.mlp_schedule(s, 0, [4], n, 0, 0)[0]] for s in range(12))
+        assert row == "CCCCC" + "R" * (n - 1) + "C" * (12 - 5 - (n - 1))
+    assert orc.start_steps_from_timesteps([900, 800, 700], [950, 800, 750, 10]) == [0, 1, 2, None]
