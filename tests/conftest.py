@@ -54,6 +54,8 @@ def golden_timestep_windows():
             p = line.split()
             if p[0] == "row":
                 rows.append((p[1], int(p[2]), p[3]))
+            elif p[0] == "mlp":
+                continue   # MLP broadcast rows: read by tests/test_oracle_module.py
             elif p[0] == "preset":
                 presets.append((p[1], int(p[2]), tuple(int(x) for x in p[3:6]), float(p[6]), float(p[7])))
             else:
