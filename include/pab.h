@@ -249,6 +249,87 @@ int pab_module_attention(pab_ctx *ctx, int block, int kind, int step, const void
                          const pab_module_weights *w, void *scratch, size_t scratch_bytes, void *hip_stream,
                          const void **out);
 
+/*
+ * MLP broadcast.  The paper applies the same idea to the MLP modules of a few
+ * blocks (Sec. 2.3, last sentence; App. A.2.1, table of MLP broadcast
+ * configurations; App. A.2.3): the output computed at each listed starting
+ * step is retained and handed to the following range-1 steps; only blocks
+ * block_lo..block_hi take part; every other (block, step) is computed.
+ *
+ * pab_mlp_schedule / pab_mlp_source_step: the decision and the step whose
+ * output is delivered (host, pure).  start_steps: n_starts step indices
+ * (0-based, denoising order).  PAB_EINVAL: negative step / block / start,
+ * range < 1, NULL list with n_starts > 0.
+ */
+int pab_mlp_schedule(int step, int block, const int *start_steps, int n_starts, int range, int block_lo,
+                     int block_hi);
+int pab_mlp_source_step(int step, int block, const int *start_steps, int n_starts, int range, int block_lo,
+                        int block_hi);
+
+/*
+ * The table gives the starting points as diffusion timesteps (1000 = start of
+ * denoising).  Maps them onto a sampler's timestep list (n_steps values that
+ * never increase): start_steps[i] = first step whose timestep is not above
+ * start_timesteps[i], or -1 if there is none.  Returns how many were found.
+ */
+int pab_steps_from_timesteps(const double *timesteps, int n_steps, const double *start_timesteps, int n_starts,
+                             int *start_steps);
+
+/*
+ * The MLP module: h = LayerNorm_C(x) * (1 + scale) + shift; u = gelu(h w1^T +
+ * b1) with GELU in its tanh form; y = u w2^T + b2.  Device pointers, bf16,
+ * dense: shift, scale [hidden]; w1 [inner, hidden]; b1 [inner] or NULL;
+ * w2 [hidden, inner]; b2 [hidden] or NULL.
+ */
+typedef struct pab_mlp_weights {
+  const void *shift, *scale;
+  const void *w1, *b1;
+  const void *w2, *b2;
+} pab_mlp_weights;
+
+/* Scratch of one MLP call: h [n_tok, hidden] and u [n_tok, inner], each rounded up to 256 bytes. */
+size_t pab_mlp_scratch_bytes(long long n_tok, int hidden, int inner);
+
+/*
+ * One MLP module, no schedule and no cache: x [n_tok, hidden] -> out
+ * [n_tok, hidden], three kernel launches on `hip_stream`.
+ * PAB_EINVAL: NULL / misaligned pointers (x, out 16 bytes; scratch 256),
+ * hidden not a multiple of 32 or > 2048, inner not a multiple of 32, a missing
+ * weight.  PAB_ENOMEM: scratch too small.  PAB_EDEVICE: launch failed.
+ */
+int pab_mlp_compute(long long n_tok, int hidden, int inner, const void *x, const pab_mlp_weights *w, void *scratch,
+                    size_t scratch_bytes, void *out, void *hip_stream);
+
+/* One run of MLP broadcasting: shapes, the schedule above, and a cache slot
+ * [n_tok, hidden] for each participating block. */
+typedef struct pab_mlp_config {
+  int n_blocks, n_steps;
+  long long n_tok;
+  int hidden, inner;
+  int n_starts, range;
+  int block_lo, block_hi;
+} pab_mlp_config;
+typedef struct pab_mlp_ctx pab_mlp_ctx;
+
+/* Bytes of the caller-owned cache: one slot per block in [block_lo, min(block_hi, n_blocks-1)]; 0 if invalid or none. */
+size_t pab_mlp_workspace_bytes(const pab_mlp_config *cfg);
+/* As pab_create: workspace 256-byte aligned, at least pab_mlp_workspace_bytes long (may be NULL if that is 0). */
+int pab_mlp_create(const pab_mlp_config *cfg, const int *start_steps, void *workspace, size_t workspace_bytes,
+                   pab_mlp_ctx **out);
+int pab_mlp_reset(pab_mlp_ctx *ctx);
+/*
+ * One MLP call of the denoising loop.  Computed: runs the module; the output
+ * goes to the block's cache slot if the block takes part, else to `y` (which
+ * must then be given).  Reused: launches nothing, reads nothing.  *out is the
+ * device pointer of the output either way.  Returns the decision or a
+ * negative status: as pab_attention, plus PAB_ESTATE if the slot does not hold
+ * the step the schedule wants to reuse.
+ */
+int pab_mlp(pab_mlp_ctx *ctx, int block, int step, const void *x, const pab_mlp_weights *w, void *scratch,
+            size_t scratch_bytes, void *y, void *hip_stream, const void **out);
+long long pab_mlp_launch_count(const pab_mlp_ctx *ctx);
+int pab_mlp_destroy(pab_mlp_ctx *ctx);
+
 /* Kernel launches issued through ctx since pab_create / the last pab_reset
  * (equals the schedule's number of computed calls); -1 if ctx is NULL. */
 long long pab_launch_count(const pab_ctx *ctx);

@@ -1,6 +1,7 @@
-// Projections of the attention module (paper App. B.5: "qkv proj", "o proj"):
-// C[M, N] = A[M, K] W[N, K]^T + bias[N], activations and weights bf16, fp32
-// accumulation on the matrix core, one rounding to bf16 on the way out.
+// Projections of the attention module (paper App. B.5: "qkv proj", "o proj")
+// and of the MLP module: C[M, N] = act(A[M, K] W[N, K]^T + bias[N]),
+// activations and weights bf16, fp32 accumulation on the matrix core, one
+// rounding to bf16 on the way out; act is nothing or the MLP's GELU.
 //
 // Both operands are contiguous along K, which is what the MFMA operands want:
 // with the weight rows as the A operand and the token rows as the B operand a
@@ -32,6 +33,7 @@ struct GemmParams {
   long long ldc;        // row pitch of C in elements
   int n_split;          // features per output plane (N: one plane; a multiple of 4)
   long long plane_stride;
+  int act;              // 0: none; 1: GELU in its tanh form, applied after the bias
   int n_mt, n_nt;       // token / feature tiles
 };
 
@@ -162,8 +164,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bias_kernel(const GemmParam
 #pragma unroll
           for (int e = 0; e < 4; ++e) bv[e] = (float)b4[e];
         }
-        Io<bf16_t>::store4(stg + j * PITCH + nl, acc[a][b][4 * rq] + bv[0], acc[a][b][4 * rq + 1] + bv[1],
-                           acc[a][b][4 * rq + 2] + bv[2], acc[a][b][4 * rq + 3] + bv[3]);
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          y[e] = acc[a][b][4 * rq + e] + bv[e];
+          if (p.act == 1) {   // 0.5 y (1 + tanh u) = y / (1 + exp(-2u)), u = sqrt(2/pi) (y + 0.044715 y^3)
+            const float u2 = -2.302208198f * (y[e] + 0.044715f * y[e] * y[e] * y[e]);   // -2 sqrt(2/pi) log2(e) (..)
+            y[e] = y[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u2));
+          }
+        }
+        Io<bf16_t>::store4(stg + j * PITCH + nl, y[0], y[1], y[2], y[3]);
       }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     // 32 rows x CHR chunks, consecutive lanes on consecutive chunks of a row

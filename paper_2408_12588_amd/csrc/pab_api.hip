@@ -2,6 +2,7 @@
 // broadcast schedule and cache bookkeeping, and the kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdint>
@@ -266,7 +267,7 @@ constexpr int GEMM_NST = 3, GEMM_WM = 2, GEMM_WN = 2, GEMM_TM = 2, GEMM_TN = 4;
 constexpr int GEMM_BM = 32 * GEMM_WM * GEMM_TM, GEMM_BN = 32 * GEMM_WN * GEMM_TN;
 
 int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
-                int n_split, long long plane_stride, hipStream_t st) {
+                int n_split, long long plane_stride, hipStream_t st, int act = 0) {
   if (!A || !W || !C) return fail(PAB_EINVAL, "A, W and C must not be NULL");
   if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(C) |
        reinterpret_cast<uintptr_t>(bias)) & 15u)
@@ -283,7 +284,7 @@ int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *b
   p.bias = static_cast<const pab::bf16_t *>(bias);
   p.C = C;
   p.M = M; p.N = N; p.K = K; p.ldc = ldc;
-  p.n_split = n_split; p.plane_stride = plane_stride;
+  p.n_split = n_split; p.plane_stride = plane_stride; p.act = act;
   p.n_mt = (M + GEMM_BM - 1) / GEMM_BM;
   p.n_nt = (N + GEMM_BN - 1) / GEMM_BN;
   // an XCD owns every eighth token tile and takes them four at a time over all feature tiles
@@ -365,9 +366,186 @@ int launch_module(int kind, int T, int S, int L, int H, int D, const void *x, co
   return PAB_OK;
 }
 
+// ---- the MLP module (paper Sec. 2.3, last sentence; App. A.2.1 MLP table) ----
+size_t mlp_scratch_bytes_of(long long n_tok, int C, int F) {
+  const size_t h = ((size_t)n_tok * C * 2 + 255) / 256 * 256, u = ((size_t)n_tok * F * 2 + 255) / 256 * 256;
+  return h + u;
+}
+
+int launch_mlp(long long n_tok, int C, int F, const void *x, const pab_mlp_weights *w, void *scratch,
+               size_t scratch_bytes, void *out, hipStream_t st) {
+  if (n_tok < 1 || C < 32 || C % 32 || C > 2048 || F < 32 || F % 32)
+    return fail(PAB_EINVAL, "n_tok=%lld, C=%d (multiple of 32, <= 2048), F=%d (multiple of 32)", n_tok, C, F);
+  if (n_tok > 0x7fffffffLL / (F > C ? F : C)) return fail(PAB_EINVAL, "too many tokens");
+  if (!x || !w || !scratch || !out) return fail(PAB_EINVAL, "x, weights, scratch and out must be non-NULL");
+  if (!w->shift || !w->scale || !w->w1 || !w->w2) return fail(PAB_EINVAL, "MLP needs shift, scale, w1 and w2");
+  if (!aligned16(x) || !aligned16(out) || (reinterpret_cast<uintptr_t>(scratch) & 255u))
+    return fail(PAB_EINVAL, "x and out must be 16-byte, scratch 256-byte aligned");
+  const size_t need = mlp_scratch_bytes_of(n_tok, C, F);
+  if (scratch_bytes < need) return fail(PAB_ENOMEM, "scratch of %zu bytes, need %zu", scratch_bytes, need);
+  unsigned char *h = static_cast<unsigned char *>(scratch);
+  unsigned char *u = h + ((size_t)n_tok * C * 2 + 255) / 256 * 256;
+  int rc;
+  if ((rc = launch_ln_modulate((int)n_tok, C, x, w->shift, w->scale, h, st)) != PAB_OK) return rc;
+  if ((rc = launch_gemm((int)n_tok, F, C, h, w->w1, w->b1, u, F, F, 0, st, 1)) != PAB_OK) return rc;
+  if ((rc = launch_gemm((int)n_tok, C, F, u, w->w2, w->b2, out, C, C, 0, st)) != PAB_OK) return rc;
+  return PAB_OK;
+}
+
 }  // namespace
 
+// context of the MLP broadcast: one slot per participating block
+struct pab_mlp_ctx {
+  pab_mlp_config cfg;
+  std::vector<int> starts;
+  unsigned char *workspace;
+  size_t slot_bytes;
+  std::vector<int> last_step;       // per block
+  std::vector<int> computed_step;   // per participating block: step whose output the slot holds
+  long long launches;
+};
+
 extern "C" {
+
+int pab_mlp_schedule(int step, int block, const int *start_steps, int n_starts, int range, int block_lo,
+                     int block_hi) {
+  if (step < 0 || block < 0) return fail(PAB_EINVAL, "step %d and block %d must be >= 0", step, block);
+  if (range < 1) return fail(PAB_EINVAL, "range %d must be >= 1", range);
+  if (n_starts < 0 || (n_starts > 0 && !start_steps)) return fail(PAB_EINVAL, "bad list of starting steps");
+  for (int i = 0; i < n_starts; ++i)
+    if (start_steps[i] < 0) return fail(PAB_EINVAL, "starting step %d is negative", start_steps[i]);
+  if (block < block_lo || block > block_hi) return PAB_COMPUTE;
+  for (int i = 0; i < n_starts; ++i)
+    if (step - start_steps[i] >= 1 && step - start_steps[i] <= range - 1) return PAB_REUSE;
+  return PAB_COMPUTE;
+}
+
+int pab_mlp_source_step(int step, int block, const int *start_steps, int n_starts, int range, int block_lo,
+                        int block_hi) {
+  const int d = pab_mlp_schedule(step, block, start_steps, n_starts, range, block_lo, block_hi);
+  if (d < 0) return d;
+  if (d == PAB_COMPUTE) return step;
+  for (int i = 0; i < n_starts; ++i)
+    if (step - start_steps[i] >= 1 && step - start_steps[i] <= range - 1) return start_steps[i];
+  return step;
+}
+
+int pab_steps_from_timesteps(const double *timesteps, int n_steps, const double *start_timesteps, int n_starts,
+                             int *start_steps) {
+  if (!timesteps || n_steps < 1 || n_starts < 0 || (n_starts > 0 && (!start_timesteps || !start_steps)))
+    return fail(PAB_EINVAL, "bad arguments");
+  for (int s = 1; s < n_steps; ++s)
+    if (timesteps[s] > timesteps[s - 1]) return fail(PAB_EINVAL, "timesteps increase at step %d", s);
+  int found = 0;
+  for (int i = 0; i < n_starts; ++i) {
+    int s = 0;
+    while (s < n_steps && timesteps[s] > start_timesteps[i]) ++s;
+    start_steps[i] = s < n_steps ? s : -1;
+    found += s < n_steps;
+  }
+  return found;
+}
+
+size_t pab_mlp_scratch_bytes(long long n_tok, int hidden, int inner) {
+  if (n_tok < 1 || hidden < 1 || inner < 1) return 0;
+  return mlp_scratch_bytes_of(n_tok, hidden, inner);
+}
+
+int pab_mlp_compute(long long n_tok, int hidden, int inner, const void *x, const pab_mlp_weights *w, void *scratch,
+                    size_t scratch_bytes, void *out, void *hip_stream) {
+  const int rc = launch_mlp(n_tok, hidden, inner, x, w, scratch, scratch_bytes, out, static_cast<hipStream_t>(hip_stream));
+  if (rc != PAB_OK) return rc;
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+  return PAB_OK;
+}
+
+size_t pab_mlp_workspace_bytes(const pab_mlp_config *c) {
+  if (!c || c->n_blocks < 1 || c->n_tok < 1 || c->hidden < 1 || c->block_lo < 0 || c->block_hi < c->block_lo) return 0;
+  const int hi = c->block_hi < c->n_blocks - 1 ? c->block_hi : c->n_blocks - 1;
+  if (hi < c->block_lo) return 0;
+  const size_t slot = ((size_t)c->n_tok * c->hidden * 2 + 255) / 256 * 256;
+  return slot * (size_t)(hi - c->block_lo + 1);
+}
+
+int pab_mlp_create(const pab_mlp_config *c, const int *start_steps, void *workspace, size_t workspace_bytes,
+                   pab_mlp_ctx **out) {
+  if (!out) return fail(PAB_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!c) return fail(PAB_EINVAL, "config is NULL");
+  if (c->n_blocks < 1 || c->n_steps < 1 || c->n_tok < 1) return fail(PAB_EINVAL, "n_blocks, n_steps, n_tok must be >= 1");
+  if (c->hidden < 32 || c->hidden % 32 || c->hidden > 2048 || c->inner < 32 || c->inner % 32)
+    return fail(PAB_EINVAL, "hidden=%d (multiple of 32, <= 2048), inner=%d (multiple of 32)", c->hidden, c->inner);
+  if (c->range < 1 || c->n_starts < 0 || (c->n_starts > 0 && !start_steps)) return fail(PAB_EINVAL, "bad range or starts");
+  if (c->block_lo < 0 || c->block_hi < c->block_lo) return fail(PAB_EINVAL, "bad block range [%d, %d]", c->block_lo, c->block_hi);
+  for (int i = 0; i < c->n_starts; ++i)
+    if (start_steps[i] < 0 || start_steps[i] >= c->n_steps) return fail(PAB_EINVAL, "starting step %d outside the run", start_steps[i]);
+  const size_t need = pab_mlp_workspace_bytes(c);
+  if (need > 0) {
+    if (!workspace) return fail(PAB_EINVAL, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(PAB_EINVAL, "workspace must be 256-byte aligned");
+    if (workspace_bytes < need) return fail(PAB_ENOMEM, "workspace of %zu bytes, need %zu", workspace_bytes, need);
+  }
+  pab_mlp_ctx *ctx = new (std::nothrow) pab_mlp_ctx;
+  if (!ctx) return fail(PAB_ENOMEM, "out of host memory");
+  ctx->cfg = *c;
+  ctx->starts.assign(start_steps, start_steps + c->n_starts);
+  ctx->workspace = static_cast<unsigned char *>(workspace);
+  ctx->slot_bytes = ((size_t)c->n_tok * c->hidden * 2 + 255) / 256 * 256;
+  ctx->last_step.assign(c->n_blocks, -1);
+  ctx->computed_step.assign(c->n_blocks, -1);
+  ctx->launches = 0;
+  *out = ctx;
+  return PAB_OK;
+}
+
+int pab_mlp_reset(pab_mlp_ctx *ctx) {
+  if (!ctx) return fail(PAB_EINVAL, "ctx is NULL");
+  std::fill(ctx->last_step.begin(), ctx->last_step.end(), -1);
+  std::fill(ctx->computed_step.begin(), ctx->computed_step.end(), -1);
+  ctx->launches = 0;
+  return PAB_OK;
+}
+
+int pab_mlp(pab_mlp_ctx *ctx, int block, int step, const void *x, const pab_mlp_weights *w, void *scratch,
+            size_t scratch_bytes, void *y, void *hip_stream, const void **out) {
+  if (!ctx) return fail(PAB_EINVAL, "ctx is NULL");
+  if (!out) return fail(PAB_EINVAL, "out is NULL");
+  *out = nullptr;
+  const pab_mlp_config &c = ctx->cfg;
+  if (block < 0 || block >= c.n_blocks) return fail(PAB_EINVAL, "block %d outside [0, %d)", block, c.n_blocks);
+  if (step < 0 || step >= c.n_steps) return fail(PAB_EINVAL, "step %d outside [0, %d)", step, c.n_steps);
+  if (step < ctx->last_step[block])
+    return fail(PAB_ESTATE, "step %d after step %d for block %d without pab_mlp_reset", step, ctx->last_step[block], block);
+  const int decision = pab_mlp_schedule(step, block, ctx->starts.data(), c.n_starts, c.range, c.block_lo, c.block_hi);
+  if (decision < 0) return decision;
+  const bool cached = block >= c.block_lo && block <= c.block_hi;
+  void *dst = cached ? ctx->workspace + ctx->slot_bytes * (size_t)(block - c.block_lo) : y;
+  if (decision == PAB_REUSE) {
+    const int src = pab_mlp_source_step(step, block, ctx->starts.data(), c.n_starts, c.range, c.block_lo, c.block_hi);
+    if (ctx->computed_step[block] != src)
+      return fail(PAB_ESTATE, "reuse at step %d needs the output of step %d, block %d holds step %d", step, src, block,
+                  ctx->computed_step[block]);
+  } else {
+    if (!dst) return fail(PAB_EINVAL, "block %d is not cached: y must be given", block);
+    const int rc = launch_mlp(c.n_tok, c.hidden, c.inner, x, w, scratch, scratch_bytes, dst, static_cast<hipStream_t>(hip_stream));
+    if (rc != PAB_OK) return rc;
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+    ctx->computed_step[block] = step;
+    ctx->launches++;
+  }
+  ctx->last_step[block] = step;
+  *out = dst;
+  return decision;
+}
+
+long long pab_mlp_launch_count(const pab_mlp_ctx *ctx) { return ctx ? ctx->launches : -1; }
+
+int pab_mlp_destroy(pab_mlp_ctx *ctx) {
+  delete ctx;
+  return PAB_OK;
+}
 
 int pab_schedule(int kind, int step, int range_lo, int range_hi, int interval) {
   if (!kind_ok(kind)) return fail(PAB_EINVAL, "kind %d is not spatial(0)/temporal(1)/cross(2)", kind);

@@ -24,6 +24,8 @@ BF16, F32 = 0, 1
 EXPORTS = (
     "pab_schedule", "pab_source_step", "pab_window_from_timesteps", "pab_preset", "pab_workspace_bytes", "pab_create", "pab_reset", "pab_attention",
     "pab_attention_compute", "pab_linear", "pab_module_scratch_bytes", "pab_module_compute", "pab_module_attention",
+    "pab_mlp_schedule", "pab_mlp_source_step", "pab_steps_from_timesteps", "pab_mlp_scratch_bytes", "pab_mlp_compute",
+    "pab_mlp_workspace_bytes", "pab_mlp_create", "pab_mlp_reset", "pab_mlp", "pab_mlp_launch_count", "pab_mlp_destroy",
     "pab_launch_count", "pab_slot_ptr", "pab_destroy", "pab_last_error",
 )
 
@@ -44,6 +46,16 @@ class pab_config(ctypes.Structure):
 class pab_module_weights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("shift", "scale", "w_qkv", "b_qkv", "gamma_q", "beta_q", "gamma_k",
                                                "beta_k", "w_kv", "b_kv", "w_o", "b_o")]
+
+
+class pab_mlp_weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("shift", "scale", "w1", "b1", "w2", "b2")]
+
+
+class pab_mlp_config(ctypes.Structure):
+    _fields_ = [("n_blocks", ctypes.c_int), ("n_steps", ctypes.c_int), ("n_tok", ctypes.c_longlong),
+                ("hidden", ctypes.c_int), ("inner", ctypes.c_int), ("n_starts", ctypes.c_int), ("range", ctypes.c_int),
+                ("block_lo", ctypes.c_int), ("block_hi", ctypes.c_int)]
 
 
 def _load() -> ctypes.CDLL:
@@ -81,6 +93,29 @@ def _load() -> ctypes.CDLL:
     lib.pab_module_attention.restype = ci
     lib.pab_module_attention.argtypes = [vp, ci, ci, ci, vp, vp, ctypes.POINTER(pab_module_weights), vp,
                                          ctypes.c_size_t, vp, ctypes.POINTER(vp)]
+    ip, dp = ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_double)
+    lib.pab_mlp_schedule.restype = ci
+    lib.pab_mlp_schedule.argtypes = [ci, ci, ip, ci, ci, ci, ci]
+    lib.pab_mlp_source_step.restype = ci
+    lib.pab_mlp_source_step.argtypes = [ci, ci, ip, ci, ci, ci, ci]
+    lib.pab_steps_from_timesteps.restype = ci
+    lib.pab_steps_from_timesteps.argtypes = [dp, ci, dp, ci, ip]
+    lib.pab_mlp_scratch_bytes.restype = ctypes.c_size_t
+    lib.pab_mlp_scratch_bytes.argtypes = [ctypes.c_longlong, ci, ci]
+    lib.pab_mlp_compute.restype = ci
+    lib.pab_mlp_compute.argtypes = [ctypes.c_longlong, ci, ci, vp, ctypes.POINTER(pab_mlp_weights), vp, ctypes.c_size_t, vp, vp]
+    lib.pab_mlp_workspace_bytes.restype = ctypes.c_size_t
+    lib.pab_mlp_workspace_bytes.argtypes = [ctypes.POINTER(pab_mlp_config)]
+    lib.pab_mlp_create.restype = ci
+    lib.pab_mlp_create.argtypes = [ctypes.POINTER(pab_mlp_config), ip, vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+    lib.pab_mlp_reset.restype = ci
+    lib.pab_mlp_reset.argtypes = [vp]
+    lib.pab_mlp.restype = ci
+    lib.pab_mlp.argtypes = [vp, ci, ci, vp, ctypes.POINTER(pab_mlp_weights), vp, ctypes.c_size_t, vp, vp, ctypes.POINTER(vp)]
+    lib.pab_mlp_launch_count.restype = ctypes.c_longlong
+    lib.pab_mlp_launch_count.argtypes = [vp]
+    lib.pab_mlp_destroy.restype = ci
+    lib.pab_mlp_destroy.argtypes = [vp]
     lib.pab_launch_count.restype = ctypes.c_longlong
     lib.pab_launch_count.argtypes = [vp]
     lib.pab_slot_ptr.restype = vp
@@ -323,3 +358,96 @@ def pab_module_compute(kind: int, x, text, w: pab_module_weights, heads: int, sc
     _check(lib.pab_module_compute(kind, T, S, L, heads, D, _ptr(x), _ptr(text) if text is not None else None,
                                   ctypes.byref(w), _ptr(scratch), scratch.numel(), _ptr(out), _stream(stream)))
     return out
+
+
+# ---- MLP broadcast ----------------------------------------------------------------------------
+def _int_array(values):
+    return (ctypes.c_int * max(len(values), 1))(*values)
+
+
+def pab_mlp_schedule(step, block, start_steps, rng, block_lo, block_hi) -> int:
+    return _check(lib.pab_mlp_schedule(step, block, _int_array(start_steps), len(start_steps), rng, block_lo, block_hi))
+
+
+def pab_mlp_source_step(step, block, start_steps, rng, block_lo, block_hi) -> int:
+    return _check(lib.pab_mlp_source_step(step, block, _int_array(start_steps), len(start_steps), rng, block_lo, block_hi))
+
+
+def pab_steps_from_timesteps(timesteps, start_timesteps):
+    """Step index of each starting timestep on the sampler's list (None where no step qualifies)."""
+    ts = (ctypes.c_double * len(timesteps))(*[float(t) for t in timesteps])
+    st = (ctypes.c_double * max(len(start_timesteps), 1))(*[float(t) for t in start_timesteps])
+    out = (ctypes.c_int * max(len(start_timesteps), 1))()
+    _check(lib.pab_steps_from_timesteps(ts, len(timesteps), st, len(start_timesteps), out))
+    return [None if out[i] < 0 else out[i] for i in range(len(start_timesteps))]
+
+
+def mlp_weights(**tensors):
+    w = pab_mlp_weights()
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        if t.dtype != torch.bfloat16:
+            raise ValueError("MLP weights are bf16")
+        setattr(w, name, _ptr(t))
+    w._keep = tensors
+    return w
+
+
+def mlp_scratch(n_tok, hidden, inner, device):
+    return torch.empty(lib.pab_mlp_scratch_bytes(n_tok, hidden, inner), dtype=torch.uint8, device=device)
+
+
+def pab_mlp_compute(x, w: pab_mlp_weights, inner: int, scratch=None, out=None, stream=None):
+    """One MLP module without schedule or cache: x ``[..., C]`` bf16 -> same shape."""
+    C = x.shape[-1]
+    n_tok = x.numel() // C
+    if scratch is None:
+        scratch = mlp_scratch(n_tok, C, inner, x.device)
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib.pab_mlp_compute(n_tok, C, inner, _ptr(x), ctypes.byref(w), _ptr(scratch), scratch.numel(), _ptr(out),
+                               _stream(stream)))
+    return out
+
+
+class MlpContext:
+    """Owns the cache slab (a torch uint8 tensor) and the library context of one MLP-broadcast run."""
+
+    def __init__(self, n_blocks, n_steps, n_tok, hidden, inner, start_steps, rng, block_lo, block_hi, device="cuda:0"):
+        self.cfg = pab_mlp_config(n_blocks, n_steps, n_tok, hidden, inner, len(start_steps), rng, block_lo, block_hi)
+        nbytes = lib.pab_mlp_workspace_bytes(ctypes.byref(self.cfg))
+        self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        handle = ctypes.c_void_p()
+        _check(lib.pab_mlp_create(ctypes.byref(self.cfg), _int_array(start_steps), _ptr(self.workspace), nbytes,
+                                  ctypes.byref(handle)))
+        self._h = handle
+        self.shape = (n_tok, hidden)
+
+    def pab_mlp(self, block, step, x, w, scratch, y=None, stream=None):
+        """-> (decision, device pointer of the output)."""
+        out = ctypes.c_void_p()
+        dec = _check(lib.pab_mlp(self._h, block, step, _ptr(x), ctypes.byref(w) if w is not None else None, _ptr(scratch),
+                                 scratch.numel() if scratch is not None else 0, _ptr(y), _stream(stream), ctypes.byref(out)))
+        return dec, out.value
+
+    def slot_tensor(self, block):
+        off = (block - self.cfg.block_lo) * ((self.shape[0] * self.shape[1] * 2 + 255) // 256 * 256)
+        return self.workspace[off:off + self.shape[0] * self.shape[1] * 2].view(torch.bfloat16).view(self.shape)
+
+    def pab_mlp_reset(self):
+        _check(lib.pab_mlp_reset(self._h))
+
+    def pab_mlp_launch_count(self) -> int:
+        return lib.pab_mlp_launch_count(self._h)
+
+    def pab_mlp_destroy(self):
+        if self._h:
+            lib.pab_mlp_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.pab_mlp_destroy()
+        except Exception:
+            pass

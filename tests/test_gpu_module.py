@@ -249,3 +249,72 @@ def test_module_full_size_sampled(pab, name):
                 want = mo.cross_attention_module(f64(x[t:t + 1, s0:s0 + 8]), f64(text), f64(w["w_qkv"]), f64(w["b_qkv"]),
                                                  f64(w["w_kv"]), f64(w["b_kv"]), f64(w["w_o"]), f64(w["b_o"]), H)
                 check_module(out[t:t + 1, s0:s0 + 8], want, "%s cross tokens (%d, %d..)" % (name, t, s0))
+
+
+# ---- MLP module and MLP broadcast --------------------------------------------------------------
+def mlp_weights_cpu(C, Fw, seed):
+    return dict(shift=bf16_randn((C,), seed + 1, 0.3), scale=bf16_randn((C,), seed + 2, 0.3),
+                w1=bf16_randn((Fw, C), seed + 3, 1.0 / math.sqrt(C)), b1=bf16_randn((Fw,), seed + 4, 0.1),
+                w2=bf16_randn((C, Fw), seed + 5, 1.0 / math.sqrt(Fw)), b2=bf16_randn((C,), seed + 6, 0.1))
+
+
+def oracle_mlp(x, w):
+    return mo.mlp_module(f64(x), f64(w["shift"]), f64(w["scale"]), f64(w["w1"]), f64(w["b1"]), f64(w["w2"]), f64(w["b2"]))
+
+
+@pytest.mark.parametrize("n_tok,C,Fw", [(300, 288, 1152), (70, 128, 512), (1, 32, 32), (515, 1152, 4608)])
+def test_mlp_module_matches_oracle(pab, n_tok, C, Fw):
+    print("mlp case", n_tok, C, Fw, flush=True)
+    x = bf16_randn((n_tok, C), 40 + n_tok)
+    w = mlp_weights_cpu(C, Fw, 50 + C)
+    wd = pab.mlp_weights(**{k: v.to(DEV) for k, v in w.items()})
+    out = pab.pab_mlp_compute(x.to(DEV), wd, Fw)
+    torch.cuda.synchronize()
+    check_module(out, oracle_mlp(x, w), "mlp module")
+
+
+def test_mlp_full_size_sampled(pab):
+    # config 2: 25440 tokens, hidden 1152, inner 4608; tokens are independent, so the oracle takes a sample of them
+    n_tok, C, Fw = 25440, 1152, 4608
+    x = bf16_randn((n_tok, C), 4242)
+    w = mlp_weights_cpu(C, Fw, 4300)
+    wd = pab.mlp_weights(**{k: v.to(DEV) for k, v in w.items()})
+    out = pab.pab_mlp_compute(x.to(DEV), wd, Fw).cpu()
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rows = np.array([0, 1, 127, 128, 12719, 25312, 25439] + list(np.random.default_rng(1).integers(0, n_tok, 40)))
+    check_module(out[rows], oracle_mlp(x[rows], w), "mlp sampled tokens")
+
+
+def test_mlp_broadcast_video(pab):
+    """Small run with MLP broadcasting: blocks 0-1 of 3 take part, starts at steps 2 and 5, range 3."""
+    from oracle import pab_oracle as orc
+    n_blocks, n_steps, n_tok, C, Fw = 3, 9, 100, 128, 512
+    starts, rng_n, blo, bhi = [2, 5], 3, 0, 1
+    ctx = pab.MlpContext(n_blocks, n_steps, n_tok, C, Fw, starts, rng_n, blo, bhi, DEV)
+    ctx.workspace.fill_(0xFF)
+    scratch = pab.mlp_scratch(n_tok, C, Fw, DEV)
+    ws = [mlp_weights_cpu(C, Fw, 7000 + 100 * b) for b in range(n_blocks)]
+    wds = [pab.mlp_weights(**{k: v.to(DEV) for k, v in w.items()}) for w in ws]
+    y = torch.empty((n_tok, C), device=DEV, dtype=torch.bfloat16)
+    last, launches = {}, 0
+    for step in range(n_steps):
+        for block in range(n_blocks):
+            x = bf16_randn((n_tok, C), 8000 + 10 * step + block)
+            want_dec, want_src = orc.mlp_schedule(step, block, starts, rng_n, blo, bhi)
+            if want_dec == 0:
+                dec, ptr = ctx.pab_mlp(block, step, x.to(DEV), wds[block], scratch, y=y if block > bhi else None)
+                launches += 1
+            else:
+                dec, ptr = ctx.pab_mlp(block, step, None, None, None)
+            torch.cuda.synchronize()
+            assert dec == want_dec, (step, block)
+            got = ctx.slot_tensor(block) if block <= bhi else y
+            assert ptr == got.data_ptr()
+            if dec == 0:
+                check_module(got, oracle_mlp(x, ws[block]), "mlp video step %d block %d" % (step, block))
+                last[block] = (step, got.clone())
+            else:
+                assert last[block][0] == want_src and torch.equal(got, last[block][1]), (step, block)
+    assert ctx.pab_mlp_launch_count() == launches == n_steps * n_blocks - 2 * 2 * 2
+    ctx.pab_mlp_destroy()

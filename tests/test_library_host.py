@@ -121,6 +121,60 @@ def test_presets_are_the_papers_table(golden_timestep_windows):
     assert pab.lib.pab_preset(0, 0, None, ctypes.byref(a), ctypes.byref(b)) == pab.EINVAL
 
 
+def test_mlp_schedule_equals_oracle():
+    rng = random.Random(17)
+    for _ in range(4000):
+        n_steps = rng.randint(1, 60)
+        starts = sorted(rng.sample(range(n_steps), rng.randint(0, min(6, n_steps))))
+        n = rng.randint(1, 5)
+        blo = rng.randint(0, 6)
+        bhi = rng.randint(blo, 10)
+        step, block = rng.randint(0, n_steps + 3), rng.randint(0, 12)
+        dec, src = orc.mlp_schedule(step, block, starts, n, blo, bhi)
+        assert pab.pab_mlp_schedule(step, block, starts, n, blo, bhi) == dec
+        assert pab.pab_mlp_source_step(step, block, starts, n, blo, bhi) == src
+    # the hand-mapped rows of the fixture file
+    with open(os.path.join(ROOT, "tests", "golden", "timestep_windows.txt")) as f:
+        rows = [l[4:].split("|") for l in f if l.startswith("mlp ")]
+    assert len(rows) == 2
+    for head, steps, pattern in rows:
+        h = head.split()
+        first, stride, n_steps, n, blo, bhi = (int(v) for v in h[1:7])
+        ts = [first - s * stride for s in range(n_steps)]
+        starts = pab.pab_steps_from_timesteps(ts, [int(v) for v in h[7:]])
+        assert starts == [int(v) for v in steps.split()] == orc.start_steps_from_timesteps(ts, [int(v) for v in h[7:]])
+        assert "".join("CR"[pab.pab_mlp_schedule(s, blo, starts, n, blo, bhi)] for s in range(n_steps)) == pattern.strip()
+    assert pab.pab_steps_from_timesteps([900, 800, 700], [950, 800, 750, 10]) == [0, 1, 2, None]
+    for args in [(-1, 0, [1], 2, 0, 1), (0, -1, [1], 2, 0, 1), (0, 0, [1], 0, 0, 1), (0, 0, [-2], 2, 0, 1)]:
+        with pytest.raises(pab.PabError):
+            pab.pab_mlp_schedule(*args)
+
+
+def test_mlp_context_errors_without_device():
+    cfg = pab.pab_mlp_config(4, 10, 64, 128, 512, 1, 2, 0, 1)
+    assert pab.lib.pab_mlp_workspace_bytes(ctypes.byref(cfg)) == 2 * 64 * 128 * 2
+    assert pab.lib.pab_mlp_scratch_bytes(64, 128, 512) == 64 * 128 * 2 + 64 * 512 * 2
+    starts = (ctypes.c_int * 1)(3)
+    h = ctypes.c_void_p()
+    fake = 0x10000
+    assert pab.lib.pab_mlp_create(ctypes.byref(cfg), starts, fake, 100, ctypes.byref(h)) == pab.ENOMEM
+    assert pab.lib.pab_mlp_create(ctypes.byref(cfg), starts, fake + 8, 1 << 20, ctypes.byref(h)) == pab.EINVAL
+    bad = pab.pab_mlp_config(4, 10, 64, 100, 512, 1, 2, 0, 1)          # hidden not a multiple of 32
+    assert pab.lib.pab_mlp_create(ctypes.byref(bad), starts, fake, 1 << 20, ctypes.byref(h)) == pab.EINVAL
+    late = (ctypes.c_int * 1)(10)                                       # starting step outside the run
+    assert pab.lib.pab_mlp_create(ctypes.byref(cfg), late, fake, 1 << 20, ctypes.byref(h)) == pab.EINVAL
+    assert pab.lib.pab_mlp_create(ctypes.byref(cfg), starts, fake, 1 << 20, ctypes.byref(h)) == pab.OK
+    out = ctypes.c_void_p()
+    w = pab.pab_mlp_weights()
+    # a reuse before anything was computed, a block out of range, a computed step without inputs
+    assert pab.lib.pab_mlp(h, 0, 4, None, None, None, 0, None, None, ctypes.byref(out)) == pab.ESTATE
+    assert pab.lib.pab_mlp(h, 4, 0, None, None, None, 0, None, None, ctypes.byref(out)) == pab.EINVAL
+    assert pab.lib.pab_mlp(h, 0, 0, None, ctypes.byref(w), None, 0, None, None, ctypes.byref(out)) == pab.EINVAL
+    assert pab.lib.pab_mlp(h, 3, 0, fake, ctypes.byref(w), fake, 1 << 20, None, None, ctypes.byref(out)) == pab.EINVAL   # uncached block, no y
+    assert pab.lib.pab_mlp_launch_count(h) == 0
+    assert pab.lib.pab_mlp_destroy(h) == pab.OK
+
+
 def test_workspace_bytes():
     cfg = pab.config_of(W.OPENSORA_480P)
     slot = 16 * 1590 * 16 * 72 * 2
