@@ -311,6 +311,23 @@ def module_section(wl, pool, args, dev):
         ms = e0.elapsed_time(e1) / reps
         per_kind[W.KIND_NAMES[kind]] = {"ms_per_call": round(ms, 4),
                                         "tflops": round(module_flops(kind) / (ms * 1e-3) / 1e12, 2)}
+    # the MLP module of a block, the other object the paper broadcasts (App. A.2.1 MLP table): per-call rate only,
+    # its schedule (three starting steps, blocks 0-4, range 2) skips 15 of 840 calls of this video
+    inner = 4 * C
+    mw = [pab.mlp_weights(shift=rn((C,), 0.3), scale=rn((C,), 0.3), w1=rn((inner, C), 1 / math.sqrt(C)), b1=rn((inner,), 0.1),
+                          w2=rn((C, inner), 1 / math.sqrt(inner)), b2=rn((C,), 0.1)) for _ in range(4)]
+    mscratch = pab.mlp_scratch(tok, C, inner, dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(8, args.kind_reps // 2)
+    for timed in (False, True):
+        if timed:
+            e0.record(stream)
+        for i in range(reps if timed else 2):
+            pab.pab_mlp_compute(xs[i % len(xs)], mw[i % 4], inner, scratch=mscratch, out=out)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    mlp_ms = e0.elapsed_time(e1) / reps
+    per_kind["mlp"] = {"ms_per_call": round(mlp_ms, 4), "tflops": round(4.0 * tok * C * inner / (mlp_ms * 1e-3) / 1e12, 2)}
     return {"object": "output of the attention module (layernorm+modulate, qkv proj, q/k layernorm, rotary, attention, o proj)",
             "value": round(flops / sec / 1e12, 3), "unit": "TFLOP/s",
             "latency_ms": {"pab": round(sec * 1e3, 3), "no_pab": round(sec0 * 1e3, 3), "steps": wl.n_steps},
