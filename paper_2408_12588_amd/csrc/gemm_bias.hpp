@@ -18,7 +18,10 @@
 // Workgroup ids go round-robin over the 8 XCDs; an XCD owns every eighth token
 // tile and walks its tiles four token tiles at a time across all feature tiles,
 // so that the weight rows in flight are shared by four workgroups and a token
-// tile's rows by all of its feature tiles inside one L2.
+// tile's rows by all of its feature tiles inside one L2.  With fewer than eight
+// token tiles that order would leave XCDs idle; the tiles are then simply
+// numbered feature-major (and the host picks a narrower feature tile so that
+// the few token rows still spread over the chip).
 #pragma once
 #include "mfma_util.hpp"
 
@@ -35,6 +38,7 @@ struct GemmParams {
   long long plane_stride;
   int act;              // 0: none; 1: GELU in its tanh form, applied after the bias
   int n_mt, n_nt;       // token / feature tiles
+  int xcd_map;          // 1: the XCD-aware tile order below; 0: tile = blockIdx.x (few token tiles)
 };
 
 // NST: ring depth.  WM x WN wavefronts per workgroup, each computing TM x TN MFMA tiles of 32 x 32
@@ -61,11 +65,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bias_kernel(const GemmParam
   const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
 
   // ---- which tile ----
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int per_group = GM * p.n_nt;
-  const int grp = slot / per_group, rem = slot % per_group;
-  const int nt_id = rem / GM;
-  const int mt_id = 8 * (grp * GM + rem % GM) + xcd;
+  int mt_id, nt_id;
+  if (p.xcd_map) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int per_group = GM * p.n_nt;
+    const int grp = slot / per_group, rem = slot % per_group;
+    nt_id = rem / GM;
+    mt_id = 8 * (grp * GM + rem % GM) + xcd;
+  } else {
+    nt_id = blockIdx.x % p.n_nt;
+    mt_id = blockIdx.x / p.n_nt;
+  }
   if (mt_id >= p.n_mt) return;
   const int m0 = mt_id * BM, n0 = nt_id * BN;
   const int M = p.M, N = p.N, K = p.K;

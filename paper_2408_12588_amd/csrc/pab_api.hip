@@ -285,14 +285,26 @@ int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *b
   p.C = C;
   p.M = M; p.N = N; p.K = K; p.ldc = ldc;
   p.n_split = n_split; p.plane_stride = plane_stride; p.act = act;
-  p.n_mt = (M + GEMM_BM - 1) / GEMM_BM;
-  p.n_nt = (N + GEMM_BN - 1) / GEMM_BN;
-  // an XCD owns every eighth token tile and takes them four at a time over all feature tiles
-  const long long owned = (p.n_mt + 7) / 8, groups = (owned + 3) / 4;
-  const long long grid = 8 * groups * 4 * p.n_nt;
+  // Few token rows (the text of a cross-attention module): 128 x 64 tiles, four wavefronts stacked along the
+  // tokens, plain tile order: four times the workgroups, spread over all XCDs.
+  const bool skinny = (long long)((M + GEMM_BM - 1) / GEMM_BM) * ((N + GEMM_BN - 1) / GEMM_BN) < 512 && (M + GEMM_BM - 1) / GEMM_BM < 8;
+  const int bm = GEMM_BM, bn = skinny ? 64 : GEMM_BN;
+  p.n_mt = (M + bm - 1) / bm;
+  p.n_nt = (N + bn - 1) / bn;
+  p.xcd_map = skinny ? 0 : 1;
+  long long grid;
+  if (skinny) {
+    grid = (long long)p.n_mt * p.n_nt;
+  } else {   // an XCD owns every eighth token tile and takes them four at a time over all feature tiles
+    const long long owned = (p.n_mt + 7) / 8, groups = (owned + 3) / 4;
+    grid = 8 * groups * 4 * p.n_nt;
+  }
   if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "matrix too large");
-  hipLaunchKernelGGL((pab::gemm_bias_kernel<GEMM_NST, GEMM_WM, GEMM_WN, GEMM_TM, GEMM_TN>), dim3((unsigned)grid),
-                     dim3(64 * GEMM_WM * GEMM_WN), 0, st, p);
+  if (skinny)
+    hipLaunchKernelGGL((pab::gemm_bias_kernel<GEMM_NST, 4, 1, 1, 2>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  else
+    hipLaunchKernelGGL((pab::gemm_bias_kernel<GEMM_NST, GEMM_WM, GEMM_WN, GEMM_TM, GEMM_TN>), dim3((unsigned)grid),
+                       dim3(64 * GEMM_WM * GEMM_WN), 0, st, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
   return PAB_OK;
