@@ -262,8 +262,9 @@ size_t module_plane_bytes(int T, int S, int L, int H, int D) {
   return ((size_t)rows * H * D * 2 + 255) / 256 * 256;
 }
 
-// projection kernel shape: 2 x 2 wavefronts of 2 x 4 MFMA tiles = 128 tokens x 256 features per workgroup
-constexpr int GEMM_NST = 3, GEMM_WM = 2, GEMM_WN = 2, GEMM_TM = 2, GEMM_TN = 4;
+// projection kernel shape: 4 x 2 wavefronts of 1 x 4 MFMA tiles = 128 tokens x 256 features per workgroup
+// (eight wavefronts measured 3% faster than four with twice the tiles each)
+constexpr int GEMM_NST = 3, GEMM_WM = 4, GEMM_WN = 2, GEMM_TM = 1, GEMM_TN = 4;
 constexpr int GEMM_BM = 32 * GEMM_WM * GEMM_TM, GEMM_BN = 32 * GEMM_WN * GEMM_TN;
 
 int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
