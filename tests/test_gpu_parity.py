@@ -225,3 +225,28 @@ def test_full_size_temporal_complete(pab):
     out = pab.pab_attention_compute(W.TEMPORAL, q.to(DEV), k.to(DEV), v.to(DEV))
     torch.cuda.synchronize()
     assert_close(out, orc.temporal(q, k, v), v, "config 2 temporal, all rows")
+
+
+def test_seeded_random_shapes(pab):
+    """Sixty seeded shapes across kinds, dtypes, head dims and all kernel variants (tile, temporal 16/24/32-row and
+    tiled fallback, cross single-pass / LDS-resident online / tiled), each compared in full with the oracle."""
+    rng = np.random.default_rng(20241127)
+    worst = 0.0
+    for case in range(60):
+        kind = int(rng.integers(0, 3))
+        D = int(rng.choice([32, 72]))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        H = int(rng.integers(1, 9))
+        if kind == W.SPATIAL:
+            T, S, L = int(rng.integers(1, 4)), int(rng.integers(1, 420)), 0
+        elif kind == W.TEMPORAL:
+            T, S, L = int(rng.integers(1, 41)), int(rng.integers(1, 60)), 0
+        else:
+            T, S, L = int(rng.integers(1, 4)), int(rng.integers(1, 200)), int(rng.choice([1, 7, 31, 32, 33, 100, 128, 129, 191, 256, 300, 511, 512, 530]))
+        print("fuzz case", case, W.KIND_NAMES[kind], T, S, L, H, D, dtype, flush=True)
+        q, k, v = rand_qkv(kind, T, S, L, H, D, dtype, seed=5000 + case)
+        out = pab.pab_attention_compute(kind, q.to(DEV), k.to(DEV), v.to(DEV))
+        torch.cuda.synchronize()
+        err = assert_close(out, orc.kind_attention(kind, q, k, v), v, "fuzz case %d" % case)
+        worst = max(worst, err / (TOL * float(v.abs().max())))
+    print("worst error / bound over the fuzz cases: %.2f" % worst)
