@@ -43,8 +43,12 @@ struct GemmParams {
 
 // NST: ring depth.  WM x WN wavefronts per workgroup, each computing TM x TN MFMA tiles of 32 x 32
 // (tokens x features): the workgroup tile is BM = 32 WM TM tokens by BN = 32 WN TN features.
-template <int NST, int WM, int WN, int TM, int TN>
+// MF: edge of the MFMA tile, 32 (v_mfma_f32_32x32x16_bf16, two per 32-column slice) or 16
+// (v_mfma_f32_16x16x32_bf16, one per slice and 16 x 16 sub-tile; it moves half the accumulator
+// data per multiply-add and sustains about 12% more under the power limit).
+template <int NST, int WM, int WN, int TM, int TN, int MF>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bias_kernel(const GemmParams p) {
+  static_assert(MF == 32 || MF == 16, "MFMA tile edge");
   constexpr int NW = WM * WN;
   constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN, BK = 32;
   constexpr int ROWS = BM + BN;                 // rows per stage: token rows, then weight rows
@@ -111,13 +115,21 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bias_kernel(const GemmParam
   const int npre = nk < NST - 1 ? nk : NST - 1;
   for (int kt = 0; kt < npre; ++kt) issue(kt, kt);
 
-  f32x16 acc[TM][TN];
+  f32x16 acc[TM][TN];                 // MF == 32: one 32 x 32 tile each
+  f32x4 acc16[2 * TM][2 * TN];        // MF == 16: 16 x 16 sub-tiles
 #pragma unroll
   for (int a = 0; a < TM; ++a)
 #pragma unroll
     for (int b = 0; b < TN; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+#pragma unroll
+  for (int a = 0; a < 2 * TM; ++a)
+#pragma unroll
+    for (int b = 0; b < 2 * TN; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc16[a][b][r] = 0.0f;
+  const int l16 = lane & 15, q16 = lane >> 4;   // MF == 16: row inside a sub-tile, 8-column chunk of the slice
 
   // fragment addresses inside a stage (elements): row * 32 + 8 * (chunk ^ swizzle(row))
   int tok_row[TM], w_row[TN];
@@ -132,6 +144,26 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bias_kernel(const GemmParam
     __syncthreads();                                   // ... everyone's share; all are done with slice kt-1
     if (kt + NST - 1 < nk) issue(kt + NST - 1, (kt + NST - 1) % NST);
     const bf16_t *st = smem + (kt % NST) * STAGE_ELEMS;
+    if (MF == 16) {
+      // operands of the 16 x 16 x 32 product: lane (l16, q16) holds row l16 of the sub-tile, columns 8 q16 .. + 7
+      bf16x8 tf[2 * TM], wf[2 * TN];
+#pragma unroll
+      for (int a = 0; a < 2 * TM; ++a) {
+        const int row = (wm * TM * 2 + a) * 16 + l16;
+        tf[a] = *reinterpret_cast<const bf16x8 *>(st + row * BK + 8 * (q16 ^ ((row >> 2) & 3)));
+      }
+#pragma unroll
+      for (int b = 0; b < 2 * TN; ++b) {
+        const int row = BM + (wn * TN * 2 + b) * 16 + l16;
+        wf[b] = *reinterpret_cast<const bf16x8 *>(st + row * BK + 8 * (q16 ^ ((row >> 2) & 3)));
+      }
+#pragma unroll
+      for (int a = 0; a < 2 * TM; ++a)
+#pragma unroll
+        for (int b = 0; b < 2 * TN; ++b)
+          acc16[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[b], tf[a], acc16[a][b], 0, 0, 0);
+      continue;
+    }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       const int q = 2 * ks + g;
@@ -167,7 +199,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bias_kernel(const GemmParam
     for (int b = 0; b < TN; ++b)
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
-        const int nl = b * 32 + 8 * rq + 4 * g;   // feature inside the block
+        // MF == 32: lane (j, g), registers 4 rq .. + 3 of tile (a, b) are features b 32 + 8 rq + 4 g + 0..3 of token j.
+        // MF == 16: rq = 2 ua + ub picks sub-tile (2 a + ua, 2 b + ub), whose four registers are features
+        //           (2 b + ub) 16 + 4 q16 + 0..3 of token ua 16 + l16.
+        const int nl = MF == 32 ? b * 32 + 8 * rq + 4 * g : (2 * b + (rq & 1)) * 16 + 4 * q16;
+        const int tl = MF == 32 ? j : (rq >> 1) * 16 + l16;   // token inside the 32-token block
         float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         if (p.bias && nw0 + nl < N) {
           const bf16x4 b4 = *reinterpret_cast<const bf16x4 *>(p.bias + nw0 + nl);
@@ -177,13 +213,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bias_kernel(const GemmParam
         float y[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          y[e] = acc[a][b][4 * rq + e] + bv[e];
+          y[e] = (MF == 32 ? acc[a][b][4 * rq + e] : acc16[2 * a + (rq >> 1)][2 * b + (rq & 1)][e]) + bv[e];
           if (p.act == 1) {   // 0.5 y (1 + tanh u) = y / (1 + exp(-2u)), u = sqrt(2/pi) (y + 0.044715 y^3)
             const float u2 = -2.302208198f * (y[e] + 0.044715f * y[e] * y[e] * y[e]);   // -2 sqrt(2/pi) log2(e) (..)
             y[e] = y[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u2));
           }
         }
-        Io<bf16_t>::store4(stg + j * PITCH + nl, y[0], y[1], y[2], y[3]);
+        Io<bf16_t>::store4(stg + tl * PITCH + nl, y[0], y[1], y[2], y[3]);
       }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     // 32 rows x CHR chunks, consecutive lanes on consecutive chunks of a row

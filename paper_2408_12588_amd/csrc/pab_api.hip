@@ -265,6 +265,7 @@ size_t module_plane_bytes(int T, int S, int L, int H, int D) {
 // projection kernel shape: 4 x 2 wavefronts of 1 x 4 MFMA tiles = 128 tokens x 256 features per workgroup
 // (eight wavefronts measured 3% faster than four with twice the tiles each)
 constexpr int GEMM_NST = 3, GEMM_WM = 4, GEMM_WN = 2, GEMM_TM = 1, GEMM_TN = 4;
+constexpr int GEMM_MF = 16;   // 16 x 16 x 32 MFMA tiles
 constexpr int GEMM_BM = 32 * GEMM_WM * GEMM_TM, GEMM_BN = 32 * GEMM_WN * GEMM_TN;
 
 int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *bias, void *C, long long ldc,
@@ -302,9 +303,9 @@ int launch_gemm(int M, int N, int K, const void *A, const void *W, const void *b
   }
   if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "matrix too large");
   if (skinny)
-    hipLaunchKernelGGL((pab::gemm_bias_kernel<GEMM_NST, 4, 1, 1, 2>), dim3((unsigned)grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((pab::gemm_bias_kernel<GEMM_NST, 4, 1, 1, 2, GEMM_MF>), dim3((unsigned)grid), dim3(256), 0, st, p);
   else
-    hipLaunchKernelGGL((pab::gemm_bias_kernel<GEMM_NST, GEMM_WM, GEMM_WN, GEMM_TM, GEMM_TN>), dim3((unsigned)grid),
+    hipLaunchKernelGGL((pab::gemm_bias_kernel<GEMM_NST, GEMM_WM, GEMM_WN, GEMM_TM, GEMM_TN, GEMM_MF>), dim3((unsigned)grid),
                        dim3(64 * GEMM_WM * GEMM_WN), 0, st, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PAB_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
