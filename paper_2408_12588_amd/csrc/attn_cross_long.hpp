@@ -153,9 +153,9 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
         b = fmaxf(fmaxf(b, S[r + 2]), S[r + 3]);
       }
       a = fmaxf(fmaxf(a, S[14]), S[15]);
-      const float mx = max_pair(fmaxf(a, b));
+      const float mx = fmaxf(a, b);   // this lane's half of the keys; m_run is shared by both lanes of a query
       if (__builtin_amdgcn_ballot_w64(mx > m_run + thr) != 0) {   // rare after the first tile
-        const float m_new = fmaxf(m_run, mx);
+        const float m_new = fmaxf(m_run, max_pair(mx));
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
         m_run = m_new;
 #pragma unroll

@@ -219,13 +219,15 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile_kernel(const TilePar
         b = fmaxf(fmaxf(b, S[n][r + 2]), S[n][r + 3]);
       }
       a = fmaxf(fmaxf(a, S[n][14]), S[n][15]);
-      mx[n] = max_pair(fmaxf(a, b));
+      mx[n] = fmaxf(a, b);   // over this lane's half of the keys; the other half sits in lane j + 32
       grow |= mx[n] > m_run[n] + thr;
     }
+    // m_run is the same in both lanes of a query: if neither lane's half exceeds it by the margin,
+    // the tile maximum does not either, and the two halves need not even be combined
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {   // rare after the first tile
 #pragma unroll
       for (int n = 0; n < NQT; ++n) {
-        const float m_new = fmaxf(m_run[n], mx[n]);
+        const float m_new = fmaxf(m_run[n], max_pair(mx[n]));
         const float alpha = __builtin_amdgcn_exp2f((m_run[n] - m_new) * c);
         m_run[n] = m_new;
 #pragma unroll
