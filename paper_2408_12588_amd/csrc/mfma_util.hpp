@@ -34,6 +34,7 @@ template <typename T> struct Io;  // element type of q, k, v, o in memory
 
 template <> struct Io<bf16_t> {
   static __device__ __forceinline__ bf16x8 load8(const bf16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
+  static __device__ __forceinline__ bf16x4 load4(const bf16_t *p) { return *reinterpret_cast<const bf16x4 *>(p); }
   static __device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d) {
     bf16x4 v;
     v[0] = (bf16_t)a; v[1] = (bf16_t)b; v[2] = (bf16_t)c; v[3] = (bf16_t)d;
@@ -50,11 +51,28 @@ template <> struct Io<float> {
     v[4] = (bf16_t)b[0]; v[5] = (bf16_t)b[1]; v[6] = (bf16_t)b[2]; v[7] = (bf16_t)b[3];
     return v;
   }
+  static __device__ __forceinline__ bf16x4 load4(const float *p) {
+    const f32x4 a = *reinterpret_cast<const f32x4 *>(p);
+    bf16x4 v;
+    v[0] = (bf16_t)a[0]; v[1] = (bf16_t)a[1]; v[2] = (bf16_t)a[2]; v[3] = (bf16_t)a[3];
+    return v;
+  }
   static __device__ __forceinline__ void store4(float *p, float a, float b, float c, float d) {
     f32x4 v = {a, b, c, d};
     *reinterpret_cast<f32x4 *>(p) = v;
   }
 };
+
+// v_mfma_f32_16x16x32_bf16: D[16x16] += A[16x32] * B[32x16].  lane l, i = l % 16, g = l / 16
+//   A operand: row i, columns 8g .. 8g+7;  B operand: column i, rows 8g .. 8g+7;  D / C: column i, rows 4g .. 4g+3
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// v_mfma_f32_16x16x16_bf16: the same with 16 columns of A / rows of B, lane (i, g) holding 4g .. 4g+3.
+__device__ __forceinline__ f32x4 mfma16_k16(bf16x4 a, bf16x4 b, f32x4 c) {
+  typedef __attribute__((ext_vector_type(4))) short s16x4;
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+}
 
 __device__ __forceinline__ bf16x8 zero8() {
   bf16x8 z;
