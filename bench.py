@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the dominant (spatial) kernel, from the rocprofv3 --pmc runs summarised in
 # profiles/attn_kernels_<workload>_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scales
 # a 1 GiB copy gives).  Not measured live: counters need the profiler.  None where no profile exists.
-PROFILED_SPATIAL_TRAFFIC_BYTES = {"opensora_480p": 394.6e6}
+PROFILED_SPATIAL_TRAFFIC_BYTES = {"opensora_480p": 414.3e6}
 
 
 def parse():
@@ -185,7 +185,7 @@ def main():
     if spatial_ms:
         avg_ms = sum(spatial_ms) / len(spatial_ms)
         achieved = wl.flops(W.SPATIAL) / (avg_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "attn_tile_kernel (spatial)", "achieved": round(achieved, 2),
+        roofline = {"bound": "mfma", "kernel": "attn_tile16_kernel (spatial)", "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                     "traffic": PROFILED_SPATIAL_TRAFFIC_BYTES.get(wl.name),
                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
