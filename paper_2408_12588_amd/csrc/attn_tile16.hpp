@@ -1,24 +1,53 @@
-// Tiled attention kernel on 16 x 16 x 32 MFMA tiles: the same work split, LDS ring and online
-// softmax as attn_tile_kernel (see there), with the products issued as v_mfma_f32_16x16x32_bf16.
-// That instruction moves half the accumulator data per multiply-add of the 32 x 32 x 16 one and
-// sustains about 12% more under the chip's power limit; 16-row output tiles also fit D + 1 = 73
-// rows of O^T in 80 instead of 96.
+// Tiled attention kernel for long query sequences (spatial and cross attention,
+// paper Sec. 2.1): o = softmax(q k^T / sqrt(D)) v per (batch, head), computed
+// with an online softmax over tiles of keys so that scores never reach memory.
 //
-// Per 32-key tile and 32-query tile a wavefront holds four 16 x 16 score sub-tiles S^T[kh][qh]
-// (key half kh, query half qh).  Lane (l16, g4) of a sub-tile owns query l16 and keys 4 g4 .. + 3:
+// Work split: one workgroup = NWV wavefronts = 32 NWV consecutive queries of one
+// (batch, head); each wavefront owns 32 queries whose q operands stay in registers.
+// Keys and values stream through a ring of NST LDS stages, one 32-key tile per
+// stage, rows packed as in memory (for bf16 inputs the global loads write LDS
+// directly, no registers in between, NST-2 tiles ahead of their use).  Several
+// workgroups share a CU, so that one wavefront's LDS and barrier waits are covered
+// by the others.
+//
+// The products are v_mfma_f32_16x16x32_bf16.  Against 32 x 32 x 16 tiles that instruction moves
+// half the accumulator data per multiply-add and sustains about 12% more under the chip's power
+// limit, and 16-row output tiles fit the D + 1 = 73 rows of O^T in 80 instead of 96.
+// Per 32-key tile a wavefront holds four 16 x 16 score sub-tiles S^T[kh][qh] (key half kh, query
+// half qh).  Lane (l16, g4) of a sub-tile owns query l16 and keys 4 g4 .. + 3:
 //   S^T[kh][qh]  = K[kh] Q[qh]^T     A = 16 key rows, B = 16 queries, 32 head-dim columns per step
-//   P^T[qh]      = exp2(c S^T - c m)  the lane's 4 + 4 probabilities of the two key halves are the
-//                                     8 k-slots of its B operand: k-slot 8 g4 + e is key 4 g4 + e
-//                                     (e < 4) or 16 + 4 g4 + e - 4
+//   P^T[qh]      = exp2(c S^T - c m)  (c = log2(e) / sqrt(D)) the lane's 4 + 4 probabilities of the
+//                                     two key halves are the 8 k-slots of its B operand: k-slot
+//                                     8 g4 + e is key 4 g4 + e (e < 4) or 16 + 4 g4 + e - 4
 //   O^T[dt][qh] += V^T[dt] P^T[qh]    A = 16 rows of V^T read transposed from the row-major tile in
 //                                     the same key order, all 32 keys in one instruction
-// Four lanes share a query (g4 = 0..3); they agree on the running maximum m and only exchange
-// their tile maxima when m has to move.
+// Keeping the query on the lane axis makes every softmax statistic a per-lane scalar, and the
+// accumulator registers of the first product are already the B operand of the second.  V rows in
+// LDS carry one extra 16-byte chunk {1, 0, ..} after their D values (written once; the staging
+// loads skip it), so row D of V^T is all ones and row D of O^T accumulates the softmax denominator
+// on the matrix core.  Four lanes share a query (g4 = 0..3) and hold the same running maximum m;
+// m is only raised when some lane's scores exceed it by more than 8 in the exponent
+// (probabilities then stay below 2^8, harmless in fp32 / bf16), and only then do the four lanes
+// exchange their tile maxima.  Numerator and denominator always share the same m, so the quotient
+// is unaffected.
+//
+// Measured no faster: software pipelining inside the wavefront (scores of tile t + 1 issued
+// before the exponentials of tile t), 64 queries per wavefront, wave priorities around the
+// matrix or the exponential phases.
 #pragma once
 #include "mfma_util.hpp"
-#include "attn_tile.hpp"
 
 namespace pab {
+
+struct TileParams {
+  const void *q, *k, *v;
+  void *o;
+  int n_batch, n_head, sq, sk;
+  long long q_bs, q_ss, k_bs, k_ss, v_bs, v_ss, o_bs, o_ss;  // batch / sequence strides, elements
+  float c;        // log2(e) / sqrt(D)
+  int n_qblk;     // query blocks per (batch, head)
+};
+
 
 // A 16-byte LDS read is served in four cycles of 16 lanes, and the lanes of a cycle are not
 // consecutive: lanes {0-3, 12-15, 20-23, 24-27} go together, then {4-7, 8-11, 16-19, 28-31}, and
@@ -35,11 +64,10 @@ template <int D> __device__ __forceinline__ int k_swizzle(int row) {
 
 template <typename T, int D, int NWV, int NST, int MINW, bool DIRECT>
 __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileParams p) {
-  constexpr int NQT = 1;
   using HD = HeadDim<D>;
   constexpr int CH = HD::CH;
   constexpr int KB = 32;             // keys per LDS stage = one MFMA tile
-  constexpr int QBLK = 32 * NQT * NWV;   // queries per workgroup
+  constexpr int QBLK = 32 * NWV;   // queries per workgroup
   constexpr int RP = D;              // row pitch of the K tile in LDS: rows packed as in memory
   constexpr int VCH = CH + 1;        // chunks per V row in LDS: CH of data, then the constant chunk {1, 0, ..}
   constexpr int VP = 8 * VCH;        // row pitch of the V tile
@@ -76,7 +104,7 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
   T *ob = reinterpret_cast<T *>(p.o) + batch * p.o_bs + (long long)head * D;
   const int sq = p.sq, sk = p.sk;
 
-  const int q_wave0 = qblk * QBLK + wave * (32 * NQT);
+  const int q_wave0 = qblk * QBLK + wave * 32;
   const bool wave_active = q_wave0 < sq;
 
   // ---- staging of key tile t into LDS stage `stage`.  The ROUNDS rounds are dealt to the

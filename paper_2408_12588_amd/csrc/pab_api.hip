@@ -15,7 +15,6 @@
 #include "attn_cross.hpp"
 #include "attn_cross_long.hpp"
 #include "attn_temporal.hpp"
-#include "attn_tile.hpp"
 #include "attn_tile16.hpp"
 #include "gemm_bias.hpp"
 #include "module_rowwise.hpp"
@@ -38,15 +37,9 @@ size_t elem_size(int dtype) { return dtype == PAB_BF16 ? 2 : 4; }
 
 // ---- launches -----------------------------------------------------------------
 
-constexpr int TILE_NQT = 1;    // 32-query tiles per wavefront
 constexpr int TILE_NWV = 8;    // wavefronts per workgroup: 256 queries share each staged K/V tile (4: 1.5-2% slower)
 constexpr int TILE_NST = 4;    // LDS ring stages (one 32-key tile each)
-constexpr bool TILE_PIPE = false;  // true: score tile t+1 before the exponentials of tile t (measured no faster)
 constexpr int TILE_MINW = 4;   // wavefronts per SIMD the register budget is sized for
-#ifndef PAB_TILE_MF
-#define PAB_TILE_MF 16
-#endif
-constexpr int TILE_MF = PAB_TILE_MF;   // MFMA tile edge of the spatial kernel: 16 (16x16x32) or 32 (32x32x16)
 
 template <typename T, int D>
 int launch_tile(int n_batch, int n_head, int sq, int sk, long long q_bs, long long q_ss, long long kv_bs,
@@ -57,7 +50,7 @@ int launch_tile(int n_batch, int n_head, int sq, int sk, long long q_bs, long lo
   p.q_bs = q_bs; p.q_ss = q_ss; p.k_bs = kv_bs; p.k_ss = kv_ss; p.v_bs = kv_bs; p.v_ss = kv_ss;
   p.o_bs = q_bs; p.o_ss = q_ss;
   p.c = (float)(1.4426950408889634 / std::sqrt((double)D));
-  constexpr int QBLK = 32 * TILE_NQT * TILE_NWV;
+  constexpr int QBLK = 32 * TILE_NWV;
   p.n_qblk = (sq + QBLK - 1) / QBLK;
   // staging addresses a 32-key tile with 32-bit byte offsets
   if (32 * kv_ss * (long long)sizeof(T) >= (1LL << 32)) return fail(PAB_EINVAL, "sequence stride too large");
@@ -65,12 +58,8 @@ int launch_tile(int n_batch, int n_head, int sq, int sk, long long q_bs, long lo
   const long long grid = (n_bh + 7) / 8 * 8 * p.n_qblk;
   if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "problem too large for one launch (%lld workgroups)", grid);
   constexpr bool DIRECT = sizeof(T) == 2;   // bf16 rows go from global memory straight into LDS
-  if (TILE_MF == 16)
-    hipLaunchKernelGGL((pab::attn_tile16_kernel<T, D, TILE_NWV, TILE_NST, TILE_MINW, DIRECT>), dim3((unsigned)grid),
-                       dim3(64 * TILE_NWV), 0, st, p);
-  else
-    hipLaunchKernelGGL((pab::attn_tile_kernel<T, D, TILE_NQT, TILE_NWV, TILE_NST, TILE_MINW, TILE_PIPE, DIRECT>),
-                       dim3((unsigned)grid), dim3(64 * TILE_NWV), 0, st, p);
+  hipLaunchKernelGGL((pab::attn_tile16_kernel<T, D, TILE_NWV, TILE_NST, TILE_MINW, DIRECT>), dim3((unsigned)grid),
+                     dim3(64 * TILE_NWV), 0, st, p);
   return PAB_OK;
 }
 
