@@ -35,6 +35,7 @@
 // before the exponentials of tile t), 64 queries per wavefront, wave priorities around the
 // matrix or the exponential phases.
 #pragma once
+#include <type_traits>
 #include "mfma_util.hpp"
 
 namespace pab {
@@ -152,6 +153,19 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
       }
     }
   };
+  auto issue_full = [&](int t, int stage) {   // the same for a tile known to lie inside the sequence
+#pragma unroll
+    for (int i = 0; i < MYR; ++i) {
+      const int round = my_round(i);
+      const bool is_k = round < PRK;
+      const long long t_off = (long long)t * KB * (is_k ? p.k_ss : p.v_ss);
+      const int lds_elem = stage * STAGE_ELEMS + (is_k ? 512 * round : TILE_ELEMS + 512 * (round - PRK));
+      if (live(i)) {
+        if (DIRECT) dma16_to_lds((is_k ? kb_ : vb) + t_off, voff[i], smem_addr + 2 * lds_elem);
+        else *reinterpret_cast<bf16x8 *>(smem + lds_elem + 8 * lane) = Io<T>::load8((is_k ? kb_ : vb) + chunk_off(i, t));
+      }
+    }
+  };
   // wait until at most `tiles` of this wavefront's staged tiles are still in flight
   auto wait_staged = [&](int tiles) {
     if (!DIRECT) return;
@@ -211,12 +225,22 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
   const int kr_off = l16 * RP + 32 * KS + 4 * g4;                       // + 16 kh * RP
   const int v_off = (4 * g4 + (l16 >> 2)) * VP + 4 * (l16 & 3);        // + 16 * VP for the second key half, + 16 dt
 
-  for (int t = 0; t < ntile; ++t) {
-    const int ahead = ntile - 1 - t;                 // staged tiles beyond t
-    wait_staged(ahead < NST - 2 ? ahead : NST - 2);  // tile t has landed (this wavefront's share)
-    __syncthreads();                                 // ... everyone's share; all are done with tile t-1
-    if (t + NST - 1 < ntile) issue(t + NST - 1, (t + NST - 1) % NST);
-    if (!wave_active) continue;
+  // One key tile.  STEADY iterations are those that find the ring full and request another whole
+  // tile: their waits and requests need no case distinctions, which keeps scalar work and branches
+  // out of the loop that runs almost all of the time.
+  auto step = [&](int t, auto steady_tag) {
+    constexpr bool STEADY = decltype(steady_tag)::value;
+    if (STEADY) {
+      wait_staged(NST - 2);
+      __syncthreads();
+      issue_full(t + NST - 1, (t + NST - 1) % NST);
+    } else {
+      const int ahead = ntile - 1 - t;                 // staged tiles beyond t
+      wait_staged(ahead < NST - 2 ? ahead : NST - 2);  // tile t has landed (this wavefront's share)
+      __syncthreads();                                 // ... everyone's share; all are done with tile t-1
+      if (t + NST - 1 < ntile) issue(t + NST - 1, (t + NST - 1) % NST);
+    }
+    if (!wave_active) return;
     const bf16_t *ktile = smem + (t % NST) * STAGE_ELEMS, *vtile = ktile + TILE_ELEMS;
 
     // ---- S^T = K Q^T, four 16 x 16 sub-tiles ----
@@ -237,7 +261,7 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
         if (REM16) S[kh][qh] = mfma16_k16(kr, qr[qh], S[kh][qh]);
       }
     }
-    if (t == ntile - 1 && (sk & 31) != 0) {   // keys past the end of the sequence take no probability mass
+    if (!STEADY && t == ntile - 1 && (sk & 31) != 0) {   // keys past the end of the sequence take no probability mass
 #pragma unroll
       for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
@@ -297,7 +321,12 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
 #pragma unroll
       for (int qh = 0; qh < 2; ++qh) oacc[dt][qh] = mfma16(vf, pf[qh], oacc[dt][qh]);
     }
-  }
+  };
+  // the last NST - 1 tiles request nothing, and a ragged last tile is requested lane by lane
+  const int n_steady = ntile - (NST - 1) - ((sk & 31) != 0 ? 1 : 0);
+  int t = 0;
+  for (; t < n_steady; ++t) step(t, std::true_type{});
+  for (; t < ntile; ++t) step(t, std::false_type{});
 
   if (wave_active) {
     // ---- epilogue: row D of O^T is the denominator; it sits in sub-tile D / 16, lane group (D % 16) / 4 ----
