@@ -44,6 +44,8 @@ SHAPES = [
     (W.SPATIAL, 1, 65, 0, 3, 72, "bf16"),      # one key past a block edge
     (W.SPATIAL, 3, 513, 0, 3, 72, "bf16"),     # more (batch, head) pairs than one per XCD round
     (W.SPATIAL, 1, 1, 0, 1, 72, "bf16"),       # single token
+    (W.SPATIAL, 1, 256, 0, 2, 72, "bf16"),     # one full query block, eight whole key tiles: steady loop, no ragged tile
+    (W.SPATIAL, 1, 257, 0, 2, 32, "bf16"),     # one query and one key past the block: a workgroup with a single live row
     (W.SPATIAL, 2, 200, 0, 2, 32, "bf16"),
     (W.SPATIAL, 2, 130, 0, 2, 72, "f32"),
     (W.SPATIAL, 4, 64, 0, 4, 32, "f32"),       # the Tiny configuration's spatial call
