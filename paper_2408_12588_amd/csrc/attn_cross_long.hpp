@@ -7,11 +7,13 @@
 // rows into LDS once (direct global -> LDS loads, row-major as in memory), and
 // then every wavefront walks over 32-query tiles of the head on its own, with
 // no further synchronisation.  Per query tile it keeps the q operands in
-// registers and runs the online softmax of the tile kernel over the key tiles:
+// registers and runs the online softmax of the tile kernel (attn_tile16.hpp:
+// 16 x 16 x 32 MFMA sub-tiles, the same lane layouts) over the key tiles:
 //   S^T = K Q^T  ->  running max (raised lazily)  ->  P^T = exp2(c (S^T - m))
 //   ->  O^T += V^T P^T, the softmax denominator riding along as row D of O^T
-// (V rows in LDS carry an extra chunk {1, 0, ..}).  K rows past L repeat row
-// L-1 and V rows past L are all zero, so padding keys need no masking.
+// (V rows in LDS carry an extra chunk {1, 0, ..}).  K rows are stored with the
+// chunk swizzle of mfma_util.hpp.  K rows past L repeat row L-1 and V rows past
+// L are all zero, so padding keys need no masking.
 #pragma once
 #include "mfma_util.hpp"
 
@@ -31,19 +33,20 @@ template <int D, int LTMAX, int NW, int MINW>
 __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const CrossLongParams p) {
   using HD = HeadDim<D>;
   using T = bf16_t;
-  constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
+  constexpr int CH = HD::CH;
   constexpr int LP = 32 * LTMAX;            // key rows of LDS capacity
   constexpr int RP = D;                     // row pitch: rows packed as in memory
   constexpr int VCH = CH + 1, VP = 8 * VCH; // V rows in LDS: CH data chunks, then the constant chunk
   constexpr int K_ELEMS = LP * RP, V_ELEMS = LP * VP;
   constexpr int SLACK = 64;                 // fragment reads of the last row run past its pitch
+  constexpr int KSWZ_CHUNKS = 4 * (D / 32); // chunks of a K row that the 16-byte operand reads cover
 
   __shared__ __attribute__((aligned(16))) bf16_t smem[K_ELEMS + V_ELEMS + SLACK];
   bf16_t *Ks = smem, *Vs = smem + K_ELEMS;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int j = lane & 31, g = lane >> 5;
+  const int l16 = lane & 15, g4 = lane >> 4;   // row / column inside a 16 x 16 sub-tile, 8-element k chunk
   const unsigned smem_addr = (unsigned)(size_t)((__attribute__((address_space(3))) char *)smem);
 
   // Workgroup ids go round-robin over the 8 XCDs; an XCD takes one contiguous eighth of the tokens
@@ -81,9 +84,11 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
     if (r < kr) {
       const int c = r * 64 + lane;
       if (c < rows * CH) {
-        int key = c / CH;
-        key = key < L ? key : L - 1;
-        dma16_to_lds(kh, (unsigned)(2 * (key * row + 8 * (c % CH))), smem_addr + 1024 * r);
+        const int krow = c / CH;
+        int chunk = c % CH;
+        if (chunk < KSWZ_CHUNKS) chunk ^= k_swizzle<D>(krow);   // the slot holds the exchanged chunk
+        const int key = krow < L ? krow : L - 1;
+        dma16_to_lds(kh, (unsigned)(2 * (key * row + 8 * chunk)), smem_addr + 1024 * r);
       }
     } else {
       const int c = (r - kr) * 64 + lane, key = c / VCH, chunk = c % VCH;
@@ -97,104 +102,140 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
     }
   }
   if (tid < SLACK / 2) reinterpret_cast<unsigned *>(smem + K_ELEMS + V_ELEMS)[tid] = 0u;
-  // The operand read of the last K row runs 8 elements past it when D is not a multiple of 16;
-  // what it finds there meets zero q columns, but has to be finite.
+  // The 16-column operand read of the last K row runs 8 elements past it when D is not a multiple
+  // of 16; what it finds there meets zero q columns, but has to be finite.
   if (rows < LP && tid < 4) reinterpret_cast<unsigned *>(Ks + rows * RP)[tid] = 0u;
   __builtin_amdgcn_s_waitcnt(0x0F70);   // this wavefront's share of K and V has landed
   __syncthreads();                      // ... everyone's
 
   const float c = p.c;
   const float thr = 8.0f / c;   // raise the running maximum only past this margin (raw score units)
-  const int k_off = sigma(j) * RP + 8 * g;                                               // + 32 kt * RP + 16 s
-  const int i16 = lane & 15, q4 = lane >> 4;
-  const int v_off = (8 * (q4 >> 1) + (i16 >> 2)) * VP + 16 * (q4 & 1) + 4 * (i16 & 3);   // + (32 kt + 16 m + 4 hh) * VP + 32 dt
-  constexpr int LDT = D / 32, LLOC = D % 32;
-  constexpr int LR = 4 * (LLOC / 8) + (LLOC % 4), LG = (LLOC / 4) & 1;
+  constexpr int REM = D % 32;
+  constexpr bool REM16 = REM > 0 && REM <= 16;   // the last columns of the first product as one 16-column step
+  constexpr int KS = REM16 ? D / 32 : (D + 31) / 32;
+  constexpr int DT16 = (D + 1 + 15) / 16;        // 16-row tiles of O^T incl. the row of the denominator
+  const int k_off = l16 * RP + 8 * (g4 ^ k_swizzle<D>(l16));        // + (32 kt + 16 kh) * RP + 32 ks
+  const int kr_off = l16 * RP + 32 * KS + 4 * g4;                   // + (32 kt + 16 kh) * RP
+  const int v_off = (4 * g4 + (l16 >> 2)) * VP + 4 * (l16 & 3);     // + 32 kt * VP, + 16 * VP for the second key half, + 16 dt
 
   const int stride = parts * NW;
   for (int t = t_lo + part * NW + wave; t < t_hi; t += stride) {
-    // ---- q operands (B): query j, columns 16 s + 8 g; tail rows load a valid row, never stored ----
-    int qrow = 32 * t + j;
-    const bool q_valid = qrow < n_tok;
-    qrow = q_valid ? qrow : n_tok - 1;
-    const T *qp = qh + (long long)qrow * row;
-    bf16x8 qf[KSTEPS];
+    // ---- q operands (B): query 16 qh + l16, columns 32 ks + 8 g4; tail rows load a valid row, never stored ----
+    bf16x8 qf[2][KS];
+    bf16x4 qr[2];
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) {
-      const int d0 = 16 * s + 8 * g;
-      qf[s] = (d0 < D) ? Io<T>::load8(qp + d0) : zero8();
+    for (int qh2 = 0; qh2 < 2; ++qh2) {
+      int qrow = 32 * t + 16 * qh2 + l16;
+      qrow = qrow < n_tok ? qrow : n_tok - 1;
+      const T *qp = qh + (long long)qrow * row;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int d0 = 32 * ks + 8 * g4;
+        qf[qh2][ks] = (d0 < D) ? Io<T>::load8(qp + d0) : zero8();
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) qr[qh2][e] = (bf16_t)0.0f;
+      if (REM16 && 32 * KS + 4 * g4 < D) qr[qh2] = Io<T>::load4(qp + 32 * KS + 4 * g4);
     }
 
-    f32x16 oacc[DT];
+    f32x4 oacc[DT16][2];
+    float m_run[2];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+    for (int qh2 = 0; qh2 < 2; ++qh2) {
+      m_run[qh2] = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.0f;
-    float m_run = -INFINITY;
+      for (int dt = 0; dt < DT16; ++dt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) oacc[dt][qh2][r] = 0.0f;
+    }
 
     for (int kt = 0; kt < ntile; ++kt) {
-      // S^T = K Q^T for 32 keys
       const bf16_t *ktile = Ks + 32 * kt * RP, *vtile = Vs + 32 * kt * VP;
-      bf16x8 kf[KSTEPS];
+      // S^T = K Q^T for 32 keys: four 16 x 16 sub-tiles (key half kh, query half)
+      f32x4 S[2][2];
 #pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) kf[s] = *reinterpret_cast<const bf16x8 *>(ktile + k_off + 16 * s);
-      f32x16 S;
+      for (int kh2 = 0; kh2 < 2; ++kh2) {
+        bf16x8 kf[KS];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) S[r] = 0.0f;
+        for (int ks = 0; ks < KS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(ktile + k_off + 16 * kh2 * RP + 32 * ks);
+        bf16x4 kr;   // columns past D read on into the next row (finite) and meet zero q columns
+        if (REM16) kr = *reinterpret_cast<const bf16x4 *>(ktile + kr_off + 16 * kh2 * RP);
 #pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) S = mfma32(kf[s], qf[s], S);
-
-      // tile maximum; the running maximum only moves when a score exceeds it by the margin
-      float a = fmaxf(fmaxf(S[0], S[1]), S[2]);
-      float b = fmaxf(fmaxf(S[3], S[4]), S[5]);
+        for (int qh2 = 0; qh2 < 2; ++qh2) {
 #pragma unroll
-      for (int r = 6; r < 14; r += 4) {
-        a = fmaxf(fmaxf(a, S[r]), S[r + 1]);
-        b = fmaxf(fmaxf(b, S[r + 2]), S[r + 3]);
-      }
-      a = fmaxf(fmaxf(a, S[14]), S[15]);
-      const float mx = fmaxf(a, b);   // this lane's half of the keys; m_run is shared by both lanes of a query
-      if (__builtin_amdgcn_ballot_w64(mx > m_run + thr) != 0) {   // rare after the first tile
-        const float m_new = fmaxf(m_run, max_pair(mx));
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        m_run = m_new;
+          for (int r = 0; r < 4; ++r) S[kh2][qh2][r] = 0.0f;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+          for (int ks = 0; ks < KS; ++ks) S[kh2][qh2] = mfma16(kf[ks], qf[qh2][ks], S[kh2][qh2]);
+          if (REM16) S[kh2][qh2] = mfma16_k16(kr, qr[qh2], S[kh2][qh2]);
+        }
       }
 
-      // P^T = exp2(c S^T - c m), already laid out as B operands; O^T += V^T P^T
-      const float mc = m_run * c;
+      // tile maximum over this lane's 8 keys per query; the four lanes of a query share m_run, which
+      // only moves when one of them exceeds it by the margin
+      float mx[2];
+      bool grow = false;
+#pragma unroll
+      for (int qh2 = 0; qh2 < 2; ++qh2) {
+        const float a = fmaxf(fmaxf(S[0][qh2][0], S[0][qh2][1]), fmaxf(S[0][qh2][2], S[0][qh2][3]));
+        const float b2 = fmaxf(fmaxf(S[1][qh2][0], S[1][qh2][1]), fmaxf(S[1][qh2][2], S[1][qh2][3]));
+        mx[qh2] = fmaxf(a, b2);
+        grow |= mx[qh2] > m_run[qh2] + thr;
+      }
+      if (__builtin_amdgcn_ballot_w64(grow) != 0) {   // rare after the first tile
+#pragma unroll
+        for (int qh2 = 0; qh2 < 2; ++qh2) {
+          float full = fmaxf(mx[qh2], __shfl_xor(mx[qh2], 16));
+          full = fmaxf(full, __shfl_xor(full, 32));
+          const float m_new = fmaxf(m_run[qh2], full);
+          const float alpha = __builtin_amdgcn_exp2f((m_run[qh2] - m_new) * c);
+          m_run[qh2] = m_new;
+#pragma unroll
+          for (int dt = 0; dt < DT16; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) oacc[dt][qh2][r] *= alpha;
+        }
+      }
+
+      // P^T = exp2(c S^T - c m): the lane's keys of the first half, then of the second, are its B operand
       bf16x8 pf[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) pf[r >> 3][r & 7] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(S[r], c, -mc));
+      for (int qh2 = 0; qh2 < 2; ++qh2) {
+        const float mc = m_run[qh2] * c;
 #pragma unroll
-      for (int m = 0; m < 2; ++m)
+        for (int kh2 = 0; kh2 < 2; ++kh2)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const bf16_t *vp = vtile + v_off + 16 * m * VP + 32 * dt;
-          const bf16x4 lo = lds_read_tr4(vp), hi = lds_read_tr4(vp + 4 * VP);
-          bf16x8 vf;
-          vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
-          vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-          oacc[dt] = mfma32(vf, pf[m], oacc[dt]);
-        }
+          for (int r = 0; r < 4; ++r)
+            pf[qh2][4 * kh2 + r] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(S[kh2][qh2][r], c, -mc));
+      }
+      // O^T += V^T P^T
+#pragma unroll
+      for (int dt = 0; dt < DT16; ++dt) {
+        const bf16_t *vp = vtile + v_off + 16 * dt;
+        const bf16x4 lo = lds_read_tr4(vp), hi = lds_read_tr4(vp + 16 * VP);
+        bf16x8 vf;
+        vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
+        vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+#pragma unroll
+        for (int qh2 = 0; qh2 < 2; ++qh2) oacc[dt][qh2] = mfma16(vf, pf[qh2], oacc[dt][qh2]);
+      }
     }
 
-    // ---- divide by the denominator held in row D of O^T, store ----
-    const float inv = 1.0f / __shfl(oacc[LDT][LR], j + 32 * LG);
-    if (q_valid) {
-      T *orow = oh + (long long)qrow * row;
+    // ---- divide by the denominator held in row D of O^T (sub-tile D / 16, lane group (D % 16) / 4), store ----
+    constexpr int DEN_DT = D / 16, DEN_G = (D % 16) / 4, DEN_R = D % 4;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+    for (int qh2 = 0; qh2 < 2; ++qh2) {
+      const float inv = 1.0f / __shfl(oacc[DEN_DT][qh2][DEN_R], l16 + 16 * DEN_G);
+      const int qrow = 32 * t + 16 * qh2 + l16;
+      if (qrow < n_tok) {
+        T *orow = oh + (long long)qrow * row;
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          const int d0 = 32 * dt + 8 * rq + 4 * g;
+        for (int dt = 0; dt < DT16; ++dt) {
+          const int d0 = 16 * dt + 4 * g4;
           if (d0 < D)
-            Io<T>::store4(orow + d0, oacc[dt][4 * rq] * inv, oacc[dt][4 * rq + 1] * inv,
-                          oacc[dt][4 * rq + 2] * inv, oacc[dt][4 * rq + 3] * inv);
+            Io<T>::store4(orow + d0, oacc[dt][qh2][0] * inv, oacc[dt][qh2][1] * inv, oacc[dt][qh2][2] * inv,
+                          oacc[dt][qh2][3] * inv);
         }
+      }
     }
   }
 }
