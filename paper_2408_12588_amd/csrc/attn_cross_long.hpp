@@ -166,7 +166,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
           for (int r = 0; r < 4; ++r) S[kh2][qh2][r] = 0.0f;
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks) S[kh2][qh2] = mfma16(kf[ks], qf[qh2][ks], S[kh2][qh2]);
-          if (REM16) S[kh2][qh2] = mfma16_k16(kr, qr[qh2], S[kh2][qh2]);
+          if (REM16) S[kh2][qh2] = mfma16_k16_chained(kr, qr[qh2], S[kh2][qh2]);
         }
       }
 

@@ -178,15 +178,6 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
   constexpr bool REM16 = REM > 0 && REM <= 16;
   constexpr int KS = REM16 ? D / 32 : (D + 31) / 32;
   constexpr int DT16 = (D + 1 + 15) / 16;    // 16-row tiles of O^T incl. the row of the denominator
-  // FOLD: the 16-column step has spare columns past D.  Column D of the K operand is set to 1 and
-  // column D of the q operand to -m (the running maximum in exp2 units, kept exactly representable
-  // in bf16), and q is scaled by c = log2(e) / sqrt(D) when it is loaded: the first product then
-  // delivers c s - m, the argument of exp2, and the vector ALU has no per-score arithmetic left but
-  // the exponential itself.  m is an arbitrary per-query shift shared by numerator and
-  // denominator, so rounding it to bf16 costs no accuracy; scaling q rounds it once more to bf16.
-  constexpr bool FOLD = REM16 && REM <= 12;
-  constexpr int FOLD_G = (D - 32 * KS) / 4;   // lane group whose first column of the 16-column step is column D
-  const float c = p.c;
   bf16x8 qf[2][KS];   // B operand of the first product: query 16 qh + l16, columns 32 ks + 8 g4 .. + 7
   bf16x4 qr[2];       // ... of the 16-column step: columns 32 KS + 4 g4 .. + 3
 #pragma unroll
@@ -200,37 +191,22 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) qr[qh][e] = (bf16_t)0.0f;
-    if (REM16) {   // every lane loads (lane groups past D from the row's last columns), then a select
-      const int d0 = 32 * KS + 4 * g4;
-      const bf16x4 ld = Io<T>::load4(qb + qrow * p.q_ss + (d0 < D ? d0 : D - 4));
-#pragma unroll
-      for (int e = 0; e < 4; ++e) qr[qh][e] = d0 < D ? ld[e] : (bf16_t)0.0f;
-    }
-    if (FOLD) {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[qh][ks][e] = (bf16_t)((float)qf[qh][ks][e] * c);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) qr[qh][e] = (bf16_t)((float)qr[qh][e] * c);
-    }
+    if (REM16 && 32 * KS + 4 * g4 < D) qr[qh] = Io<T>::load4(qb + qrow * p.q_ss + 32 * KS + 4 * g4);
   }
-  bf16x4 kr_fixed;   // FOLD: what the lane groups past D feed as K columns: 1 in column D, else 0
-#pragma unroll
-  for (int e = 0; e < 4; ++e) kr_fixed[e] = (bf16_t)((e == 0 && g4 == FOLD_G) ? 1.0f : 0.0f);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the q loads outside the loop (the staging loads are invisible to the compiler)
 
   f32x4 oacc[DT16][2];
   float m_run[2];
 #pragma unroll
   for (int qh = 0; qh < 2; ++qh) {
-    m_run[qh] = FOLD ? 0.0f : -INFINITY;   // FOLD: in exp2 units, set by the first tile
+    m_run[qh] = -INFINITY;
 #pragma unroll
     for (int dt = 0; dt < DT16; ++dt)
 #pragma unroll
       for (int r = 0; r < 4; ++r) oacc[dt][qh][r] = 0.0f;
   }
 
+  const float c = p.c;
   const float thr = 8.0f / c;   // raise the running maximum only past this margin (raw score units)
   const int k_off = l16 * RP + 8 * (g4 ^ k_swizzle<D>(l16));             // + 16 kh * RP + 32 ks
   const int kr_off = l16 * RP + 32 * KS + 4 * g4;                       // + 16 kh * RP
@@ -261,23 +237,15 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
       bf16x8 kf[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(ktile + k_off + 16 * kh * RP + 32 * ks);
-      bf16x4 kr = kr_fixed;
-      if (REM16) {   // lane groups past D read on into the next row: finite; FOLD replaces what they read
-        typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
-        const u32x2 ld = *reinterpret_cast<const u32x2 *>(ktile + kr_off + 16 * kh * RP);
-        const u32x2 fx = __builtin_bit_cast(u32x2, kr_fixed);
-        u32x2 sel;
-        sel[0] = (!FOLD || g4 < FOLD_G) ? ld[0] : fx[0];
-        sel[1] = (!FOLD || g4 < FOLD_G) ? ld[1] : fx[1];
-        kr = __builtin_bit_cast(bf16x4, sel);
-      }
+      bf16x4 kr;   // columns past D (lane groups whose q columns are zero) read on into the next row: finite
+      if (REM16) kr = *reinterpret_cast<const bf16x4 *>(ktile + kr_off + 16 * kh * RP);
 #pragma unroll
       for (int qh = 0; qh < 2; ++qh) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) S[kh][qh][r] = 0.0f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) S[kh][qh] = mfma16(kf[ks], qf[qh][ks], S[kh][qh]);
-        if (REM16) S[kh][qh] = mfma16_k16(kr, qr[qh], S[kh][qh]);
+        if (REM16) S[kh][qh] = mfma16_k16_chained(kr, qr[qh], S[kh][qh]);
       }
     }
     if (!STEADY && t == ntile - 1 && (sk & 31) != 0) {   // keys past the end of the sequence take no probability mass
@@ -300,30 +268,16 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
       const float a = fmaxf(fmaxf(S[0][qh][0], S[0][qh][1]), fmaxf(S[0][qh][2], S[0][qh][3]));
       const float b = fmaxf(fmaxf(S[1][qh][0], S[1][qh][1]), fmaxf(S[1][qh][2], S[1][qh][3]));
       mx[qh] = fmaxf(a, b);
-      grow |= FOLD ? mx[qh] > 8.0f : mx[qh] > m_run[qh] + thr;
+      grow |= mx[qh] > m_run[qh] + thr;
     }
-    if (__builtin_amdgcn_ballot_w64(grow) != 0 || (FOLD && t == 0)) {   // rare after the first tile
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {   // rare after the first tile
 #pragma unroll
       for (int qh = 0; qh < 2; ++qh) {
         float full = fmaxf(mx[qh], __shfl_xor(mx[qh], 16));
         full = fmaxf(full, __shfl_xor(full, 32));
-        float alpha;
-        if (FOLD) {   // the scores are relative to m already: move m by the (bf16-rounded) excess
-          const float want = t == 0 ? full : fmaxf(full, 0.0f);
-          const float m_new = (float)(bf16_t)(m_run[qh] + want);
-          const float moved = m_new - m_run[qh];
-          alpha = __builtin_amdgcn_exp2f(-moved);
-          m_run[qh] = m_new;
-#pragma unroll
-          for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) S[kh][qh][r] -= moved;
-          if (g4 == FOLD_G) qr[qh][0] = (bf16_t)(-m_new);
-        } else {
-          const float m_new = fmaxf(m_run[qh], full);
-          alpha = __builtin_amdgcn_exp2f((m_run[qh] - m_new) * c);
-          m_run[qh] = m_new;
-        }
+        const float m_new = fmaxf(m_run[qh], full);
+        const float alpha = __builtin_amdgcn_exp2f((m_run[qh] - m_new) * c);
+        m_run[qh] = m_new;
 #pragma unroll
         for (int dt = 0; dt < DT16; ++dt)
 #pragma unroll
@@ -340,7 +294,7 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
       for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          pf[qh][4 * kh + r] = (bf16_t)__builtin_amdgcn_exp2f(FOLD ? S[kh][qh][r] : __builtin_fmaf(S[kh][qh][r], c, -mc));
+          pf[qh][4 * kh + r] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(S[kh][qh][r], c, -mc));
     }
 
     // ---- O^T += V^T P^T: 16 rows of V^T over all 32 keys per instruction ----

@@ -229,6 +229,28 @@ def test_full_size_temporal_complete(pab):
     assert_close(out, orc.temporal(q, k, v), v, "config 2 temporal, all rows")
 
 
+def test_long_spatial_and_long_text_shapes(pab):
+    """Seeded shapes where the steady loops of the tiled kernels run many times: spatial attention with up to
+    2600 tokens (both dtypes, both head dims, 5% of the query rows scaled x8 in some of the bf16 cases), and cross
+    attention over 129..512 text tokens, each compared in full with the oracle."""
+    rng = np.random.default_rng(20241128)
+    worst = 0.0
+    cases = []
+    for i in range(14):
+        cases.append((W.SPATIAL, 1, int(rng.integers(257, 2601)), 0, int(rng.integers(1, 3)), int(rng.choice([72, 72, 32])),
+                      "bf16" if i % 3 else "f32", 0.05 if i % 2 and i % 3 else 0.0))
+    for L in (129, 191, 192, 193, 255, 256, 257, 319, 320, 321, 400, 511, 512):
+        cases.append((W.CROSS, 1, int(rng.integers(33, 400)), L, int(rng.integers(1, 5)), 72, "bf16", 0.05 if L % 2 else 0.0))
+    for n, (kind, T, S, L, H, D, dtype, peaked) in enumerate(cases):
+        print("long case", n, W.KIND_NAMES[kind], T, S, L, H, D, dtype, peaked, flush=True)
+        q, k, v = rand_qkv(kind, T, S, L, H, D, dtype, seed=7000 + n, scale_rows=peaked)
+        out = pab.pab_attention_compute(kind, q.to(DEV), k.to(DEV), v.to(DEV))
+        torch.cuda.synchronize()
+        err = assert_close(out, orc.kind_attention(kind, q, k, v), v, "long case %d" % n)
+        worst = max(worst, err / (TOL * float(v.abs().max())))
+    print("worst error / bound over the long cases: %.2f" % worst)
+
+
 def test_seeded_random_shapes(pab):
     """Sixty seeded shapes across kinds, dtypes, head dims and all kernel variants (tile, temporal 16/24/32-row and
     tiled fallback, cross single-pass / LDS-resident online / tiled), each compared in full with the oracle."""
