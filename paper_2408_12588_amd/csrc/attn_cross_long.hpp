@@ -151,23 +151,31 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
 
     for (int kt = 0; kt < ntile; ++kt) {
       const bf16_t *ktile = Ks + 32 * kt * RP, *vtile = Vs + 32 * kt * VP;
-      // S^T = K Q^T for 32 keys: four 16 x 16 sub-tiles (key half kh, query half)
+      // S^T = K Q^T for 32 keys: four 16 x 16 sub-tiles (key half kh, query half); the 32-column steps of
+      // all four first, then the 16-column steps (see mfma_shape_change)
       f32x4 S[2][2];
+      bf16x4 kr[2];
 #pragma unroll
       for (int kh2 = 0; kh2 < 2; ++kh2) {
         bf16x8 kf[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(ktile + k_off + 16 * kh2 * RP + 32 * ks);
-        bf16x4 kr;   // columns past D read on into the next row (finite) and meet zero q columns
-        if (REM16) kr = *reinterpret_cast<const bf16x4 *>(ktile + kr_off + 16 * kh2 * RP);
+        // columns past D read on into the next row (finite) and meet zero q columns
+        if (REM16) kr[kh2] = *reinterpret_cast<const bf16x4 *>(ktile + kr_off + 16 * kh2 * RP);
 #pragma unroll
         for (int qh2 = 0; qh2 < 2; ++qh2) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) S[kh2][qh2][r] = 0.0f;
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks) S[kh2][qh2] = mfma16(kf[ks], qf[qh2][ks], S[kh2][qh2]);
-          if (REM16) S[kh2][qh2] = mfma16_k16_chained(kr, qr[qh2], S[kh2][qh2]);
         }
+      }
+      if (REM16) {
+        mfma_shape_change(S[0][0], S[0][1], S[1][0], S[1][1]);
+#pragma unroll
+        for (int kh2 = 0; kh2 < 2; ++kh2)
+#pragma unroll
+          for (int qh2 = 0; qh2 < 2; ++qh2) S[kh2][qh2] = mfma16_k16(kr[kh2], qr[qh2], S[kh2][qh2]);
       }
 
       // tile maximum over this lane's 8 keys per query; the four lanes of a query share m_run, which

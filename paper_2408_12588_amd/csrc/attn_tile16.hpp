@@ -230,23 +230,31 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
     if (!wave_active) return;
     const bf16_t *ktile = smem + (t % NST) * STAGE_ELEMS, *vtile = ktile + TILE_ELEMS;
 
-    // ---- S^T = K Q^T, four 16 x 16 sub-tiles ----
+    // ---- S^T = K Q^T, four 16 x 16 sub-tiles: the 32-column steps of all four first, then (after the wait
+    //      states that a change of MFMA shape on an accumulator needs, see mfma_util.hpp) the 16-column steps ----
     f32x4 S[2][2];
+    bf16x4 kr[2];
 #pragma unroll
     for (int kh = 0; kh < 2; ++kh) {
       bf16x8 kf[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(ktile + k_off + 16 * kh * RP + 32 * ks);
-      bf16x4 kr;   // columns past D (lane groups whose q columns are zero) read on into the next row: finite
-      if (REM16) kr = *reinterpret_cast<const bf16x4 *>(ktile + kr_off + 16 * kh * RP);
+      // columns past D (lane groups whose q columns are zero) read on into the next row: finite
+      if (REM16) kr[kh] = *reinterpret_cast<const bf16x4 *>(ktile + kr_off + 16 * kh * RP);
 #pragma unroll
       for (int qh = 0; qh < 2; ++qh) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) S[kh][qh][r] = 0.0f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) S[kh][qh] = mfma16(kf[ks], qf[qh][ks], S[kh][qh]);
-        if (REM16) S[kh][qh] = mfma16_k16_chained(kr, qr[qh], S[kh][qh]);
       }
+    }
+    if (REM16) {
+      mfma_shape_change(S[0][0], S[0][1], S[1][0], S[1][1]);
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int qh = 0; qh < 2; ++qh) S[kh][qh] = mfma16_k16(kr[kh], qr[qh], S[kh][qh]);
     }
     if (!STEADY && t == ntile - 1 && (sk & 31) != 0) {   // keys past the end of the sequence take no probability mass
 #pragma unroll

@@ -74,15 +74,14 @@ __device__ __forceinline__ f32x4 mfma16_k16(bf16x4 a, bf16x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
 }
 
-// The same, accumulating onto the result of a 16 x 16 x 32 product.  On gfx950 a 16 x 16 x 16 MFMA that takes the
-// result of a 16 x 16 x 32 one as its C operand (or the other way round) needs more wait states than hipcc 7.2
-// leaves between the two: with the instructions in source order (-mllvm -enable-misched=0) every such chain
-// returned wrong sums, and in scheduled builds it depended on what the scheduler happened to put in between.
-// About ten wait states are enough (four on top of the compiler's passed every test); the s_nop below is tied
-// to the accumulator by a data dependence, so no schedule can move it away.
-__device__ __forceinline__ f32x4 mfma16_k16_chained(bf16x4 a, bf16x4 b, f32x4 c) {
-  asm volatile("s_nop 7" : "+v"(c));
-  return mfma16_k16(a, b, c);
+// On gfx950 a 16 x 16 x 16 MFMA that takes the result of a 16 x 16 x 32 one as its C operand (or the other way
+// round) needs more wait states than hipcc 7.2 leaves between the two: with the instructions in source order
+// (-mllvm -enable-misched=0) every such chain returned wrong sums, and in scheduled builds it depended on what the
+// scheduler happened to put in between.  About ten wait states are enough (four on top of the compiler's passed
+// every test).  Call this between the last 16 x 16 x 32 MFMA and the first 16 x 16 x 16 one on the given
+// accumulators: the s_nop is tied to them by a data dependence, so no schedule can move it away.
+__device__ __forceinline__ void mfma_shape_change(f32x4 &a, f32x4 &b, f32x4 &c, f32x4 &d) {
+  asm volatile("s_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
 __device__ __forceinline__ bf16x8 zero8() {
