@@ -44,6 +44,7 @@ def parse():
     ap.add_argument("--pool", type=int, default=8, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-module", action="store_true", help="skip the module-level section")
+    ap.add_argument("--videos", type=int, default=1, help="timed videos when --steps is not given (steps = videos x the workload's steps)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--kind-reps", type=int, default=40, help="launches per kind in the per-kind section")
     ap.add_argument("--profile-kind", default=None, choices=["spatial", "temporal", "cross"],
@@ -65,7 +66,7 @@ def main():
     from paper_2408_12588_amd import pab, workloads as W
 
     wl = W.BY_NAME[args.workload]
-    K = args.steps if args.steps is not None else wl.n_steps
+    K = args.steps if args.steps is not None else wl.n_steps * max(1, args.videos)
     Wm = args.warmup if args.warmup is not None else wl.n_steps
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -95,8 +96,9 @@ def main():
             k, v = kv_cross[i % args.pool]
         return q, k, v
 
-    def run_steps(ctx, first_step, n, events=None):
-        """Queue n denoising steps asynchronously; returns computed FLOPs per kind."""
+    def run_steps(ctx, first_step, n, events=None, marks=None):
+        """Queue n denoising steps asynchronously; returns computed FLOPs per kind.  marks collects one
+        stream event at the start of every video and one after the last step."""
         flops = [0.0, 0.0, 0.0]
         launches = [0, 0, 0]
         i = first_step * len(calls)
@@ -104,6 +106,9 @@ def main():
             step = s % wl.n_steps
             if step == 0:
                 ctx.pab_reset()
+                if marks is not None:
+                    marks.append(torch.cuda.Event(enable_timing=True))
+                    marks[-1].record(stream)
             for block, kind in calls:
                 q, k, v = inputs(i, kind)
                 i += 1
@@ -120,14 +125,24 @@ def main():
                 if dec == pab.COMPUTE:
                     flops[kind] += wl.flops(kind)
                     launches[kind] += 1
+        if marks is not None:
+            marks.append(torch.cuda.Event(enable_timing=True))
+            marks[-1].record(stream)
         return flops, launches
 
-    def timed(ctx, n, events=None):
+    def timed(ctx, n, events=None, marks=None):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        flops, launches = run_steps(ctx, 0, n, events)
+        flops, launches = run_steps(ctx, 0, n, events, marks)
         torch.cuda.synchronize()
         return time.perf_counter() - t0, flops, launches
+
+    def per_video_ms(marks, n):
+        """Latencies of the whole videos inside n timed steps (stream events at the video boundaries)."""
+        if n % wl.n_steps or len(marks) < 2:
+            return None
+        ms = [a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:])]
+        return {"per_video": [round(x, 3) for x in ms], "median": round(sorted(ms)[len(ms) // 2], 3)}
 
     # ---- PAB schedule: warmup, then the timed region ----
     if args.profile_kind:
@@ -148,8 +163,8 @@ def main():
 
     ctx = pab.PabContext(pab.config_of(wl), dev)
     run_steps(ctx, 0, Wm)
-    events = []
-    sec, flops, launches = timed(ctx, K, events)
+    events, marks = [], []
+    sec, flops, launches = timed(ctx, K, events, marks)
     spatial_ms = [a.elapsed_time(b) for a, b in events]
     total_flops = sum(flops)
     ctx.pab_destroy()
@@ -157,7 +172,8 @@ def main():
     # ---- same library, broadcast ranges 1/1/1: the no-PAB baseline ----
     ctx0 = pab.PabContext(pab.config_of(wl, (1, 1, 1)), dev, workspace=ctx.workspace)
     run_steps(ctx0, 0, min(Wm, 2))
-    sec0, flops0, launches0 = timed(ctx0, K)
+    marks0 = []
+    sec0, flops0, launches0 = timed(ctx0, K, None, marks0)
     ctx0.pab_destroy()
 
     # ---- per-kind section: back-to-back computes of one kind over the rotating pool ----
@@ -216,7 +232,8 @@ def main():
                    "intervals": list(wl.intervals), "window": [wl.lo, wl.hi], "input_pool": args.pool},
         "value_definition": "attention FLOPs actually computed under the PAB schedule / wall time of the timed steps",
         "roofline": roofline,
-        "latency_ms": {"pab": round(sec * 1e3, 3), "no_pab": round(sec0 * 1e3, 3), "steps": K},
+        "latency_ms": {"pab": round(sec * 1e3, 3), "no_pab": round(sec0 * 1e3, 3), "steps": K,
+                       "videos_pab": per_video_ms(marks, K), "videos_no_pab": per_video_ms(marks0, K)},
         "pab": {"time_reduction": round(time_reduction, 4), "skipped_flop_fraction": round(skipped_flop_fraction, 4),
                 "gap_abs": round(time_reduction - skipped_flop_fraction, 4),
                 "gap_rel": round((time_reduction - skipped_flop_fraction) / skipped_flop_fraction, 4) if skipped_flop_fraction else None,
