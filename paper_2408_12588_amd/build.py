@@ -40,5 +40,17 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+def device_asm(path: str, extra_flags=()) -> str:
+    """Write the gfx950 assembly of the device code (same flags as the library) to `path`."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [hipcc] + flags + list(extra_flags) + ["-S", "--cuda-device-only", "-o", path] + SOURCES
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + "\n")
+        raise RuntimeError("hipcc failed writing the device assembly")
+    return path
+
+
 if __name__ == "__main__":
     print(build_lib(verbose=True))
