@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--pool", type=int, default=8, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-module", action="store_true", help="skip the module-level section")
+    ap.add_argument("--no-mfma-reference", action="store_true",
+                    help="skip the library GEMM that shows what the matrix core sustains on this box")
     ap.add_argument("--videos", type=int, default=1, help="timed videos when --steps is not given (steps = videos x the workload's steps)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--kind-reps", type=int, default=40, help="launches per kind in the per-kind section")
@@ -243,11 +245,41 @@ def main():
                 "effective_tflops": round(sum(flops0) / sec / 1e12, 3)},
         "kinds": kinds,
     }
+    if not args.no_mfma_reference and wl.dtype == "bf16":
+        result["mfma_reference"] = mfma_reference(dev)
     if not args.no_module and wl.dtype == "bf16":
         result["module"] = module_section(wl, pool, args, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     print(json.dumps(result), flush=True)
+
+
+def mfma_reference(dev, n=8192, reps=20):
+    """Context for the roofline fraction, not part of the path: the vendor library's plain bf16 GEMM
+    (torch.matmul, n x n x n) on this machine, on N(0,1) operands and on all-zero ones.  The published peak
+    assumes the full shader clock; under its power limit the chip does not hold it on real data, and
+    this is the rate a dense contraction with no softmax in it sustains here."""
+    import torch
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    stream = torch.cuda.current_stream()
+    res = {"what": "torch.matmul bf16 %d^3 (vendor library), %d back-to-back calls" % (n, reps), "unit": "TFLOP/s"}
+    for name, scale in (("normal", 1.0), ("zeros", 0.0)):
+        a = [(torch.randn((n, n), generator=gen, device=dev) * scale).to(torch.bfloat16) for _ in range(2)]
+        b = [(torch.randn((n, n), generator=gen, device=dev) * scale).to(torch.bfloat16) for _ in range(2)]
+        c = torch.empty((n, n), device=dev, dtype=torch.bfloat16)
+        for i in range(3):
+            torch.matmul(a[i % 2], b[i % 2], out=c)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(reps):
+            torch.matmul(a[i % 2], b[i % 2], out=c)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        tf = 2.0 * n ** 3 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        res[name] = round(tf, 1)
+        res[name + "_frac_of_peak"] = round(tf / PEAK_BF16_TFLOPS, 4)
+    return res
 
 
 def module_section(wl, pool, args, dev):
