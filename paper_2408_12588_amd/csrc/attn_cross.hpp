@@ -53,7 +53,12 @@ __global__ __launch_bounds__(64 * NW) void attn_cross_kernel(const CrossParams p
   constexpr int KSTEPS = HD::KSTEPS, DT = HD::DT, CH = HD::CH;
   constexpr int LP = 32 * LT;               // key rows held in LDS
   constexpr int RP = D;                     // row pitch: rows packed as in memory
-  constexpr int VCH = CH + 1, VP = 8 * VCH; // V rows in LDS: CH data chunks, then the constant chunk
+  // V rows in LDS: CH data chunks, the constant chunk, then zero chunks up to a pitch of 96 elements = 48 banks.
+  // A transposed 8-byte read takes 64 bytes from each of four consecutive rows per half wavefront; with rows
+  // 48 banks apart these four stretches are the four quarters of the 64 banks (0, 48, 32, 16), with the 40 banks
+  // of the minimal pitch the fourth overlapped the first (every such read took twice as long).
+  constexpr int VCH = 12, VP = 8 * VCH;
+  static_assert(CH + 1 <= VCH, "head dim too long for the V row pitch");
   constexpr int K_ELEMS = LP * RP, V_ELEMS = LP * VP, KV_ELEMS = K_ELEMS + V_ELEMS;
   constexpr int QB_ELEMS = 32 * RP;         // one tile buffer
   constexpr int NCHUNK = 32 * CH;           // 16-byte chunks of a tile
