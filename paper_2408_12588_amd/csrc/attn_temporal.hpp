@@ -40,7 +40,9 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
   constexpr int QK_BYTES = (QDIRECT ? 1 : 2) * RT * DKP * 2;   // k (and q) staging
   constexpr int O_BYTES = RT * OP * (int)sizeof(T_);
   constexpr int A_BYTES = QK_BYTES > O_BYTES ? QK_BYTES : O_BYTES;   // q/k staging, reused for o
-  constexpr int V_BYTES = RT * DKP * 2;
+  constexpr int VP = 96;                  // pitch of the V rows: 48 banks, so that the four rows of a transposed read do not meet
+  static_assert(D + 8 <= VP, "head dim too long for the V row pitch");
+  constexpr int V_BYTES = RT * VP * 2;
   constexpr int WAVE_BYTES = A_BYTES + V_BYTES;
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * WAVE_BYTES];
@@ -51,13 +53,18 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
   bf16_t *Qs = reinterpret_cast<bf16_t *>(base);                   // [RT][DKP] (unused with QDIRECT)
   bf16_t *Ks = QDIRECT ? Qs : Qs + RT * DKP;                       // [RT][DKP]
   T_ *Os = reinterpret_cast<T_ *>(base);                           // [RT][OP], aliases Qs/Ks
-  bf16_t *Vs = reinterpret_cast<bf16_t *>(base + A_BYTES);         // [RT][DKP], rows >= T stay zero
+  bf16_t *Vs = reinterpret_cast<bf16_t *>(base + A_BYTES);         // [RT][VP], rows >= T stay zero; column D is 1
 
   const int T = p.T;
   const float c = p.c;
 
   // value rows of frames that do not exist must be finite: zero the tile once
-  for (int idx = lane; idx < RT * DKP / 8; idx += 64) reinterpret_cast<bf16x8 *>(Vs)[idx] = zero8();
+  // and column D of every row is 1, so that row D of V^T sums the probabilities (the softmax denominator)
+  for (int idx = lane; idx < RT * VP / 8; idx += 64) {
+    bf16x8 fill = zero8();
+    if (idx % (VP / 8) == D / 8) fill[D % 8] = (bf16_t)1.0f;
+    reinterpret_cast<bf16x8 *>(Vs)[idx] = fill;
+  }
 
   // Workgroup ids go round-robin over the 8 XCDs.  Give every XCD a contiguous run of problems:
   // four neighbouring heads are 4.5 cache lines, so neighbouring workgroups share a line, and this
@@ -99,7 +106,7 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
       if (cidx < T * CHZ) {
         if (!QDIRECT) *reinterpret_cast<bf16x8 *>(&Qs[t * DKP + 8 * cc]) = q8[i];
         *reinterpret_cast<bf16x8 *>(&Ks[t * DKP + 8 * cc]) = k8[i];
-        if (cc < CH) *reinterpret_cast<bf16x8 *>(&Vs[t * DKP + 8 * cc]) = v8[i];
+        if (cc < CH) *reinterpret_cast<bf16x8 *>(&Vs[t * VP + 8 * cc]) = v8[i];
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -133,20 +140,23 @@ __global__ __launch_bounds__(256) void attn_temporal_kernel(const TemporalParams
 
     // ---- O^T = V^T P^T; the A operand is gathered column-wise from the row-major tile ----
     f32x16 o[DT];
+    // Two transposed 8-byte reads give lane (j, g) row 32 dt + j of V^T over keys 16 m + 8 g .. + 7: within 16
+    // lanes, lane i receives element i of the rows that lanes 4 e .. 4 e + 3 address (e = 0 .. 3).  Rows past the
+    // staging area alias its last row: such keys weigh 0.
+    const int i16 = lane & 15, q4 = lane >> 4;
+    const int vcol = 16 * (q4 & 1) + 4 * (i16 & 3);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
-      const int d = 32 * dt + j;
 #pragma unroll
       for (int m = 0; m < NM; ++m) {
+        const int row = 16 * m + 8 * (q4 >> 1) + (i16 >> 2);
+        const bf16x4 lo = lds_read_tr4(Vs + min(row, RT - 1) * VP + vcol + 32 * dt);
+        const bf16x4 hi = lds_read_tr4(Vs + min(row + 4, RT - 1) * VP + vcol + 32 * dt);
         bf16x8 vf;
-        if (d < D) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) vf[e] = Vs[min(16 * m + 8 * g + e, RT - 1) * DKP + d];   // keys >= T weigh 0
-        } else {
-          vf = (d == D) ? splat8(1.0f) : zero8();   // row D of V^T: all ones -> softmax denominator
-        }
+        vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
+        vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
         o[dt] = mfma32(vf, pf[m], o[dt]);
       }
     }
