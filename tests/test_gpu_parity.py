@@ -107,6 +107,35 @@ def test_peaked_queries_small(pab):
         assert_close(out, orc.kind_attention(kind, q, k, v), v, "peaked %d" % kind)
 
 
+def test_launches_follow_the_callers_stream(pab):
+    # Two side streams (default priority) work on different inputs at once; each result is read after
+    # synchronising only its own stream, and the scheduled call on a side stream leaves its slot filled.
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    cases = [(W.SPATIAL, 2, 300, 0), (W.TEMPORAL, 16, 50, 0), (W.CROSS, 2, 150, 120)]
+    data = [rand_qkv(kind, T, S, L, 2, 72, "bf16", seed=300 + i) for i, (kind, T, S, L) in enumerate(cases)]
+    dev = [tuple(x.to(DEV) for x in d) for d in data]
+    torch.cuda.synchronize()
+    outs = []
+    for i, ((kind, T, S, L), (q, k, v)) in enumerate(zip(cases, dev)):
+        st = (s1, s2)[i % 2]
+        out = torch.full_like(q, float("nan"))
+        st.wait_stream(torch.cuda.current_stream())     # the fill above ran on the current stream
+        pab.pab_attention_compute(kind, q, k, v, out=out, stream=st)
+        outs.append((st, out))
+    for (st, out), (kind, T, S, L), (q, k, v) in zip(outs, cases, data):
+        st.synchronize()
+        assert_close(out, orc.kind_attention(kind, q, k, v), v, "side stream %d" % kind)
+    wl = W.TINY
+    ctx = pab.PabContext(pab.config_of(wl), DEV)
+    q, k, v = W.make_qkv(wl, 0, W.SPATIAL, 0)
+    with torch.cuda.stream(s1):
+        dec, _ = ctx.pab_attention(0, W.SPATIAL, 0, q.to(DEV), k.to(DEV), v.to(DEV))
+    s1.synchronize()
+    assert dec == pab.COMPUTE
+    assert_close(ctx.slot_tensor(0, W.SPATIAL), orc.kind_attention(W.SPATIAL, q, k, v), v, "scheduled call on a side stream")
+    ctx.pab_destroy()
+
+
 def test_identical_keys_give_mean_of_values(pab):
     T, S, H, D = 1, 200, 2, 72
     q, k, v = rand_qkv(W.SPATIAL, T, S, 0, H, D, "bf16", seed=5)
