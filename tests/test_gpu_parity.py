@@ -136,6 +136,36 @@ def test_launches_follow_the_callers_stream(pab):
     ctx.pab_destroy()
 
 
+def test_compute_calls_replay_from_a_graph(pab):
+    # The library neither allocates nor synchronises, so a run of launches can be captured once and replayed
+    # (what a launch-bound loop such as the Tiny video wants).  Only this library's kernels are recorded; the
+    # inputs are refreshed by eager copies between the replays and every replay is checked.
+    cases = [(W.SPATIAL, 2, 300, 0), (W.TEMPORAL, 16, 50, 0), (W.CROSS, 2, 150, 120), (W.CROSS, 2, 150, 200)]
+    shapes = [rand_qkv(kind, T, S, L, 2, 72, "bf16", seed=1) for kind, T, S, L in cases]
+    static_in = [tuple(torch.empty_like(x, device=DEV) for x in d) for d in shapes]
+    static_out = [torch.empty_like(d[0], device=DEV) for d in shapes]
+    for (kind, T, S, L), (q, k, v), out in zip(cases, static_in, static_out):   # warm-up outside the capture
+        q.zero_(); k.zero_(); v.zero_()
+        pab.pab_attention_compute(kind, q, k, v, out=out)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for (kind, T, S, L), (q, k, v), out in zip(cases, static_in, static_out):
+            pab.pab_attention_compute(kind, q, k, v, out=out)
+    for rep in range(3):
+        data = [rand_qkv(kind, T, S, L, 2, 72, "bf16", seed=400 + 10 * rep + i) for i, (kind, T, S, L) in enumerate(cases)]
+        for dst, src in zip(static_in, data):
+            for a, b in zip(dst, src):
+                a.copy_(b)
+        for out in static_out:
+            out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (kind, T, S, L), (q, k, v), out in zip(cases, data, static_out):
+            assert_close(out, orc.kind_attention(kind, q, k, v), v, "replay %d kind %d" % (rep, kind))
+
+
 def test_identical_keys_give_mean_of_values(pab):
     T, S, H, D = 1, 200, 2, 72
     q, k, v = rand_qkv(W.SPATIAL, T, S, 0, H, D, "bf16", seed=5)
