@@ -451,8 +451,8 @@ def cpu_baseline(wl, target_seconds):
             "sample": "%s; fp64; %s; value = computed FLOPs of one video under the schedule / its extrapolated time"
                       % (wl.name, "; ".join(samples)),
             "seconds": round(total_sec, 2), "sample_tflops": round(total_fl / total_sec / 1e12, 6),
-            "sec_per_call": {W.KIND_NAMES[kd]: round(sc, 4) for kd, sc in sec_per_call.items()},
-            "video_seconds_extrapolated": {"pab": round(video["pab"][0], 1), "no_pab": round(video["no_pab"][0], 1)}}
+            "sec_per_call": {W.KIND_NAMES[kd]: round(sc, 6) for kd, sc in sec_per_call.items()},
+            "video_seconds_extrapolated": {"pab": round(video["pab"][0], 3), "no_pab": round(video["no_pab"][0], 3)}}
 
 
 if __name__ == "__main__":
