@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the dominant (spatial) kernel, from the rocprofv3 --pmc runs summarised in
 # profiles/attn_kernels_<workload>_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scales
 # a 1 GiB copy gives).  Not measured live: counters need the profiler.  None where no profile exists.
-PROFILED_SPATIAL_TRAFFIC_BYTES = {"opensora_480p": 415.9e6}
+PROFILED_SPATIAL_TRAFFIC_BYTES = {"opensora_480p": 416.1e6}
 
 
 def parse():
