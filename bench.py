@@ -360,7 +360,7 @@ def module_section(wl, pool, args, dev):
         ms = e0.elapsed_time(e1) / reps
         per_kind[W.KIND_NAMES[kind]] = {"ms_per_call": round(ms, 4),
                                         "tflops": round(module_flops(kind) / (ms * 1e-3) / 1e12, 2)}
-    # the MLP module of a block, the other object the paper broadcasts (App. A.2.1 MLP table): per-call rate only,
+    # the MLP module of a block, the other object the paper broadcasts (App. A.2.2 MLP table): per-call rate only,
     # its schedule (three starting steps, blocks 0-4, range 2) skips 15 of 840 calls of this video
     inner = 4 * C
     mw = [pab.mlp_weights(shift=rn((C,), 0.3), scale=rn((C,), 0.3), w1=rn((inner, C), 1 / math.sqrt(C)), b1=rn((inner,), 0.1),

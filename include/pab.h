@@ -44,7 +44,7 @@ enum pab_decision { PAB_COMPUTE = 0, PAB_REUSE = 1 };
 enum pab_status {
   PAB_OK = 0,
   PAB_EINVAL = -1,  /* bad argument: kind, step, block, shape, dtype, alignment, NULL */
-  PAB_ESTATE = -2,  /* reuse asked of a slot never written; step went backwards      */
+  PAB_ESTATE = -2,  /* reuse of a slot that does not hold its source step; step went backwards */
   PAB_ENOMEM = -3,  /* workspace smaller than pab_workspace_bytes()                  */
   PAB_EDEVICE = -4  /* a HIP call failed                                             */
 };
@@ -79,7 +79,7 @@ typedef struct pab_ctx pab_ctx;
  * multiple of interval (the period is anchored at the first step of the
  * window); outside the window it is always computed.
  * Returns PAB_COMPUTE or PAB_REUSE; PAB_EINVAL if kind is not a pab_kind,
- * step < 0, interval < 1 or range_lo > range_hi.  `kind` does not change the
+ * step < 0, interval < 1, range_lo < 0 or range_lo > range_hi.  `kind` does not change the
  * decision (the per-kind range is the caller's `interval`); it is validated.
  */
 int pab_schedule(int kind, int step, int range_lo, int range_hi, int interval);
@@ -152,8 +152,10 @@ int pab_reset(pab_ctx *ctx);
  * Returns the decision taken (PAB_COMPUTE / PAB_REUSE) or a negative status:
  * PAB_EINVAL (NULL ctx/out, block or kind or step out of range, kind absent
  * from the config, NULL or misaligned q/k/v on a computed step), PAB_ESTATE
- * (reuse of a slot never written, or step smaller than the last step seen for
- * this (block, kind) since the last reset), PAB_EDEVICE (launch failed).
+ * (reuse at a step whose source step, pab_source_step, is not the step the
+ * slot holds -- never written, or the caller skipped that computed step -- or
+ * a step smaller than the last step seen for this (block, kind) since the
+ * last reset), PAB_EDEVICE (launch failed).
  * Never synchronises.
  */
 int pab_attention(pab_ctx *ctx, int block, int kind, int step, const void *q, const void *k,
@@ -187,10 +189,12 @@ int pab_linear(int M, int N, int K, const void *A, const void *W, const void *bi
 
 /*
  * The paper broadcasts the output of the whole attention MODULE, so that a
- * reused step also skips what surrounds the attention operation (App. B.6:
- * x -> q,k,v = proj(x) -> q,k = pos_emb(layer_norm(q,k)) -> o = attn(q,k,v)
- * -> o = proj(o); App. B.5 lists the parts: layernorm1, modulate, qkv proj,
- * layernorm2, pos emb, attn, o proj).  The three calls below are that module
+ * reused step also skips what surrounds the attention operation (the workflow
+ * of App. B.6: the hidden states are projected to queries, keys and values,
+ * queries and keys are normalised and given their position embedding, the
+ * attention operation runs, and its result goes through the output
+ * projection; App. B.5 lists the parts it times: layernorm1, modulate, qkv
+ * proj, layernorm2, pos emb, attn, o proj).  The three calls below are that module
  * with its output as the cached object; they use the same context, schedule
  * and cache slots as pab_attention (a slot holds [T, S, C], C = heads *
  * head_dim, the same bytes as an attention output).  bf16 only.
@@ -251,8 +255,8 @@ int pab_module_attention(pab_ctx *ctx, int block, int kind, int step, const void
 
 /*
  * MLP broadcast.  The paper applies the same idea to the MLP modules of a few
- * blocks (Sec. 2.3, last sentence; App. A.2.1, table of MLP broadcast
- * configurations; App. A.2.3): the output computed at each listed starting
+ * blocks (Sec. 2.3, last sentence; App. A.2.2, table of MLP broadcast
+ * configurations; App. B.2): the output computed at each listed starting
  * step is retained and handed to the following range-1 steps; only blocks
  * block_lo..block_hi take part; every other (block, step) is computed.
  *
@@ -313,7 +317,9 @@ typedef struct pab_mlp_ctx pab_mlp_ctx;
 
 /* Bytes of the caller-owned cache: one slot per block in [block_lo, min(block_hi, n_blocks-1)]; 0 if invalid or none. */
 size_t pab_mlp_workspace_bytes(const pab_mlp_config *cfg);
-/* As pab_create: workspace 256-byte aligned, at least pab_mlp_workspace_bytes long (may be NULL if that is 0). */
+/* As pab_create: workspace 256-byte aligned, at least pab_mlp_workspace_bytes long (may be NULL if that is 0).
+ * PAB_EINVAL also when two different starting steps are closer than `range`: the later one would fall among the
+ * reused steps of the earlier one, and the steps after it would name a source that is never computed. */
 int pab_mlp_create(const pab_mlp_config *cfg, const int *start_steps, void *workspace, size_t workspace_bytes,
                    pab_mlp_ctx **out);
 int pab_mlp_reset(pab_mlp_ctx *ctx);
@@ -328,10 +334,16 @@ int pab_mlp_reset(pab_mlp_ctx *ctx);
 int pab_mlp(pab_mlp_ctx *ctx, int block, int step, const void *x, const pab_mlp_weights *w, void *scratch,
             size_t scratch_bytes, void *y, void *hip_stream, const void **out);
 long long pab_mlp_launch_count(const pab_mlp_ctx *ctx);
+/* Device pointer of the cache slot of a participating block (block_lo <= block
+ * <= block_hi), NULL for any other block or a NULL ctx.  Borrowed, read-only. */
+const void *pab_mlp_slot_ptr(const pab_mlp_ctx *ctx, int block);
 int pab_mlp_destroy(pab_mlp_ctx *ctx);
 
-/* Kernel launches issued through ctx since pab_create / the last pab_reset
- * (equals the schedule's number of computed calls); -1 if ctx is NULL. */
+/* Computed calls issued through ctx since pab_create / the last pab_reset: one
+ * per call of pab_attention / pab_module_attention that the schedule decided
+ * to compute (an operation-level call is one kernel launch, a module-level
+ * call four or five); equals the schedule's number of computed steps.  -1 if
+ * ctx is NULL. */
 long long pab_launch_count(const pab_ctx *ctx);
 
 /* Device pointer of slot (block, kind) without touching any state, or NULL. */

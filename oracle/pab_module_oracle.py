@@ -1,8 +1,9 @@
 """fp64 oracle of the attention MODULE whose output PAB broadcasts.  TEST INFRASTRUCTURE ONLY.
 
 The paper broadcasts the output of the whole attention module, so that a reused step skips
-everything inside it (App. B.6: "x -> q,k,v = proj(x) -> q,k = pos_emb(layer_norm(q,k)) ->
-o = attn(q,k,v) -> o = proj(o)"); App. B.5 lists the parts it timed: layernorm1, mask, modulate,
+everything inside it (the workflow of App. B.6: project the hidden states to queries, keys and
+values, normalise queries and keys and apply the position embedding, run the attention operation,
+project its result); App. B.5 lists the parts it timed: layernorm1, mask, modulate,
 qkv proj, layernorm2, pos emb (temporal only), attn, o proj, reshape (self attention) and
 qkv proj, attn, o proj, reshape (cross attention).  The paper names these parts and gives no
 formulas; each function below states the reading it takes.  Everything is written as the plain
@@ -110,7 +111,7 @@ def gelu_tanh(x: np.ndarray) -> np.ndarray:
 
 def mlp_module(x, shift, scale, w1, b1, w2, b2) -> np.ndarray:
     """The MLP module of a transformer block, the other object the paper broadcasts (Sec. 2.3 last
-    sentence, App. A.2.1 MLP table): layernorm + modulate as in the attention modules, a projection
+    sentence, App. A.2.2 MLP table): layernorm + modulate as in the attention modules, a projection
     to the inner width, the activation, a projection back.  x: [..., C]; w1: [F, C]; w2: [C, F]."""
     h = modulate(layer_norm(x), shift, scale)
     return linear(gelu_tanh(linear(h, w1, b1)), w2, b2)

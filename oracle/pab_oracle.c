@@ -108,8 +108,8 @@ long pab_oracle_window(const double *timesteps, long n_steps, double t_start,
 }
 
 /*
- * Broadcast schedule of the MLP modules (App. A.2.1, table of MLP broadcast
- * configurations; App. A.2.3 for the reason): the output computed at each of a
+ * Broadcast schedule of the MLP modules (App. A.2.2, table of MLP broadcast
+ * configurations; App. B.2 for the reason): the output computed at each of a
  * few listed starting steps is retained and handed to the following steps of
  * its broadcast range n, i.e. to the n-1 steps after the starting step; only
  * blocks block_lo..block_hi take part.  Everything else is computed.

@@ -98,7 +98,7 @@ def schedule_row(n_steps: int, lo: int, hi: int, n: int) -> str:
 
 
 def mlp_schedule(step: int, block: int, starts, n: int, block_lo: int, block_hi: int):
-    """(decision, source step) of the MLP broadcast (paper App. A.2.1, MLP table): 0 computed, 1 reused."""
+    """(decision, source step) of the MLP broadcast (paper App. A.2.2, MLP table): 0 computed, 1 reused."""
     arr = (ctypes.c_long * max(len(starts), 1))(*starts)
     src = ctypes.c_long(-1)
     r = _load().pab_oracle_mlp_schedule(step, block, arr, len(starts), n, block_lo, block_hi, ctypes.byref(src))

@@ -107,7 +107,7 @@ __device__ __forceinline__ void dma16_to_lds(const void *base, unsigned voff, un
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(voff), "s"(base), "s"(lds_addr)
-               : "memory");
+               : "memory", "m0");
 }
 
 __device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {

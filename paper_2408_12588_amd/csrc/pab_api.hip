@@ -239,8 +239,12 @@ int schedule_cell(pab_ctx *ctx, int block, int kind, int step, void **slot) {
                 ctx->last_step[cell], block, kind);
   const int decision = pab_schedule(kind, step, c.range_lo, c.range_hi, c.interval[kind]);
   if (decision < 0) return decision;
-  if (decision == PAB_REUSE && ctx->computed_step[cell] < 0)
-    return fail(PAB_ESTATE, "reuse at step %d but block %d kind %d was never computed", step, block, kind);
+  if (decision == PAB_REUSE) {   // the slot must hold the step that Eq. 1 broadcasts from
+    const int src = pab_source_step(kind, step, c.range_lo, c.range_hi, c.interval[kind]);
+    if (ctx->computed_step[cell] != src)
+      return fail(PAB_ESTATE, "reuse at step %d needs the output of step %d, block %d kind %d holds step %d", step, src,
+                  block, kind, ctx->computed_step[cell]);
+  }
   *slot = const_cast<void *>(pab_slot_ptr(ctx, block, kind));
   return decision;
 }
@@ -378,7 +382,7 @@ int launch_module(int kind, int T, int S, int L, int H, int D, const void *x, co
   return PAB_OK;
 }
 
-// ---- the MLP module (paper Sec. 2.3, last sentence; App. A.2.1 MLP table) ----
+// ---- the MLP module (paper Sec. 2.3, last sentence; App. A.2.2 MLP table) ----
 size_t mlp_scratch_bytes_of(long long n_tok, int C, int F) {
   const size_t h = ((size_t)n_tok * C * 2 + 255) / 256 * 256, u = ((size_t)n_tok * F * 2 + 255) / 256 * 256;
   return h + u;
@@ -492,6 +496,14 @@ int pab_mlp_create(const pab_mlp_config *c, const int *start_steps, void *worksp
   if (c->block_lo < 0 || c->block_hi < c->block_lo) return fail(PAB_EINVAL, "bad block range [%d, %d]", c->block_lo, c->block_hi);
   for (int i = 0; i < c->n_starts; ++i)
     if (start_steps[i] < 0 || start_steps[i] >= c->n_steps) return fail(PAB_EINVAL, "starting step %d outside the run", start_steps[i]);
+  // two broadcasts must not overlap: a start inside another start's reused steps would itself be reused,
+  // and the steps after it would then name a source that was never computed
+  for (int i = 0; i < c->n_starts; ++i)
+    for (int j = 0; j < c->n_starts; ++j)
+      if (i != j && start_steps[j] != start_steps[i] && start_steps[j] - start_steps[i] >= 1 &&
+          start_steps[j] - start_steps[i] <= c->range - 1)
+        return fail(PAB_EINVAL, "starting steps %d and %d are closer than the broadcast range %d", start_steps[i],
+                    start_steps[j], c->range);
   const size_t need = pab_mlp_workspace_bytes(c);
   if (need > 0) {
     if (!workspace) return fail(PAB_EINVAL, "workspace is NULL");
@@ -532,7 +544,7 @@ int pab_mlp(pab_mlp_ctx *ctx, int block, int step, const void *x, const pab_mlp_
   const int decision = pab_mlp_schedule(step, block, ctx->starts.data(), c.n_starts, c.range, c.block_lo, c.block_hi);
   if (decision < 0) return decision;
   const bool cached = block >= c.block_lo && block <= c.block_hi;
-  void *dst = cached ? ctx->workspace + ctx->slot_bytes * (size_t)(block - c.block_lo) : y;
+  void *dst = cached ? const_cast<void *>(pab_mlp_slot_ptr(ctx, block)) : y;
   if (decision == PAB_REUSE) {
     const int src = pab_mlp_source_step(step, block, ctx->starts.data(), c.n_starts, c.range, c.block_lo, c.block_hi);
     if (ctx->computed_step[block] != src)
@@ -554,6 +566,11 @@ int pab_mlp(pab_mlp_ctx *ctx, int block, int step, const void *x, const pab_mlp_
 
 long long pab_mlp_launch_count(const pab_mlp_ctx *ctx) { return ctx ? ctx->launches : -1; }
 
+const void *pab_mlp_slot_ptr(const pab_mlp_ctx *ctx, int block) {
+  if (!ctx || block < ctx->cfg.block_lo || block > ctx->cfg.block_hi || block >= ctx->cfg.n_blocks) return nullptr;
+  return ctx->workspace + ctx->slot_bytes * (size_t)(block - ctx->cfg.block_lo);
+}
+
 int pab_mlp_destroy(pab_mlp_ctx *ctx) {
   delete ctx;
   return PAB_OK;
@@ -563,7 +580,8 @@ int pab_schedule(int kind, int step, int range_lo, int range_hi, int interval) {
   if (!kind_ok(kind)) return fail(PAB_EINVAL, "kind %d is not spatial(0)/temporal(1)/cross(2)", kind);
   if (step < 0) return fail(PAB_EINVAL, "step %d is negative", step);
   if (interval < 1) return fail(PAB_EINVAL, "interval %d must be >= 1", interval);
-  if (range_lo > range_hi) return fail(PAB_EINVAL, "window [%d, %d] is empty", range_lo, range_hi);
+  if (range_lo < 0 || range_lo > range_hi)
+    return fail(PAB_EINVAL, "window [%d, %d] must satisfy 0 <= lo <= hi", range_lo, range_hi);
   if (step < range_lo || step > range_hi) return PAB_COMPUTE;
   return ((step - range_lo) % interval == 0) ? PAB_COMPUTE : PAB_REUSE;
 }

@@ -25,7 +25,8 @@ EXPORTS = (
     "pab_schedule", "pab_source_step", "pab_window_from_timesteps", "pab_preset", "pab_workspace_bytes", "pab_create", "pab_reset", "pab_attention",
     "pab_attention_compute", "pab_linear", "pab_module_scratch_bytes", "pab_module_compute", "pab_module_attention",
     "pab_mlp_schedule", "pab_mlp_source_step", "pab_steps_from_timesteps", "pab_mlp_scratch_bytes", "pab_mlp_compute",
-    "pab_mlp_workspace_bytes", "pab_mlp_create", "pab_mlp_reset", "pab_mlp", "pab_mlp_launch_count", "pab_mlp_destroy",
+    "pab_mlp_workspace_bytes", "pab_mlp_create", "pab_mlp_reset", "pab_mlp", "pab_mlp_launch_count", "pab_mlp_slot_ptr",
+    "pab_mlp_destroy",
     "pab_launch_count", "pab_slot_ptr", "pab_destroy", "pab_last_error",
 )
 
@@ -114,6 +115,8 @@ def _load() -> ctypes.CDLL:
     lib.pab_mlp.argtypes = [vp, ci, ci, vp, ctypes.POINTER(pab_mlp_weights), vp, ctypes.c_size_t, vp, vp, ctypes.POINTER(vp)]
     lib.pab_mlp_launch_count.restype = ctypes.c_longlong
     lib.pab_mlp_launch_count.argtypes = [vp]
+    lib.pab_mlp_slot_ptr.restype = vp
+    lib.pab_mlp_slot_ptr.argtypes = [vp, ci]
     lib.pab_mlp_destroy.restype = ci
     lib.pab_mlp_destroy.argtypes = [vp]
     lib.pab_launch_count.restype = ctypes.c_longlong
@@ -432,7 +435,11 @@ class MlpContext:
         return dec, out.value
 
     def slot_tensor(self, block):
-        off = (block - self.cfg.block_lo) * ((self.shape[0] * self.shape[1] * 2 + 255) // 256 * 256)
+        """View of the cache slot of a participating block inside the workspace tensor (no copy)."""
+        p = lib.pab_mlp_slot_ptr(self._h, block)
+        if not p:
+            raise PabError(EINVAL, "block %d has no MLP cache slot" % block)
+        off = p - self.workspace.data_ptr()
         return self.workspace[off:off + self.shape[0] * self.shape[1] * 2].view(torch.bfloat16).view(self.shape)
 
     def pab_mlp_reset(self):

@@ -89,8 +89,9 @@ def test_linear_argument_errors(pab):
 # Bound: the attention operation is held to 1e-2 * max|V|; around it sit projections whose inputs
 # and outputs are stored in bf16 (2^-9 relative each, averaging out over the K = C terms of a
 # product) and whose weights have rows of about unit norm, so the module output carries an
-# error of the size of the attention error: 2e-2 * max|y| leaves a factor of two.
-TOL_MODULE = 2e-2
+# error of the size of the attention error and is held to the same bar, 1e-2 * max|y|
+# (observed: 4-5e-3).
+TOL_MODULE = 1e-2
 
 
 def self_weights(C, heads, seed):

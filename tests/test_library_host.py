@@ -55,7 +55,8 @@ def test_schedule_fuzz_against_oracle():
 
 
 def test_schedule_errors():
-    for args in [(3, 0, 0, 5, 2), (-1, 0, 0, 5, 2), (0, -1, 0, 5, 2), (0, 0, 0, 5, 0), (0, 0, 6, 5, 2)]:
+    for args in [(3, 0, 0, 5, 2), (-1, 0, 0, 5, 2), (0, -1, 0, 5, 2), (0, 0, 0, 5, 0), (0, 0, 6, 5, 2),
+                 (0, 0, -1, 5, 2), (0, 2**31 - 1, -2**31, 5, 2)]:   # a negative window start is refused, not wrapped
         assert pab.lib.pab_schedule(*args) == pab.EINVAL
         assert pab.lib.pab_source_step(*args) == pab.EINVAL
         assert pab.pab_last_error() != ""
@@ -163,7 +164,20 @@ def test_mlp_context_errors_without_device():
     assert pab.lib.pab_mlp_create(ctypes.byref(bad), starts, fake, 1 << 20, ctypes.byref(h)) == pab.EINVAL
     late = (ctypes.c_int * 1)(10)                                       # starting step outside the run
     assert pab.lib.pab_mlp_create(ctypes.byref(cfg), late, fake, 1 << 20, ctypes.byref(h)) == pab.EINVAL
+    # two broadcasts that overlap (starts closer than the range) are refused; the same start twice is one broadcast
+    wide = pab.pab_mlp_config(4, 10, 64, 128, 512, 2, 3, 0, 1)
+    assert pab.lib.pab_mlp_create(ctypes.byref(wide), (ctypes.c_int * 2)(3, 4), fake, 1 << 20, ctypes.byref(h)) == pab.EINVAL
+    assert "closer than the broadcast range" in pab.pab_last_error()
+    assert pab.lib.pab_mlp_create(ctypes.byref(wide), (ctypes.c_int * 2)(5, 3), fake, 1 << 20, ctypes.byref(h)) == pab.EINVAL
+    assert pab.lib.pab_mlp_create(ctypes.byref(wide), (ctypes.c_int * 2)(3, 6), fake, 1 << 20, ctypes.byref(h)) == pab.OK
+    assert pab.lib.pab_mlp_destroy(h) == pab.OK
+    assert pab.lib.pab_mlp_create(ctypes.byref(wide), (ctypes.c_int * 2)(3, 3), fake, 1 << 20, ctypes.byref(h)) == pab.OK
+    assert pab.lib.pab_mlp_destroy(h) == pab.OK
     assert pab.lib.pab_mlp_create(ctypes.byref(cfg), starts, fake, 1 << 20, ctypes.byref(h)) == pab.OK
+    # slots of the participating blocks 0 and 1, none for the others
+    assert pab.lib.pab_mlp_slot_ptr(h, 0) == fake and pab.lib.pab_mlp_slot_ptr(h, 1) == fake + 64 * 128 * 2
+    assert pab.lib.pab_mlp_slot_ptr(h, 2) is None and pab.lib.pab_mlp_slot_ptr(h, -1) is None
+    assert pab.lib.pab_mlp_slot_ptr(None, 0) is None
     out = ctypes.c_void_p()
     w = pab.pab_mlp_weights()
     # a reuse before anything was computed, a block out of range, a computed step without inputs
@@ -229,7 +243,7 @@ def test_create_and_attention_errors_without_device():
     assert pab.lib.pab_attention(None, 0, 0, 0, 16, 16, 16, None, ctypes.byref(out)) == pab.EINVAL
     # step 3 of the tiny spatial row is a reuse step, but nothing was computed yet
     assert att(0, 0, 3, None, None, None, None) == pab.ESTATE
-    assert "never computed" in pab.pab_last_error()
+    assert "needs the output of step 2" in pab.pab_last_error() and "holds step -1" in pab.pab_last_error()
     assert pab.lib.pab_launch_count(h) == 0
     # slots are laid out block-major, kind-minor
     slot = 4 * 64 * 4 * 32 * 4

@@ -214,7 +214,7 @@ def test_cross_module_against_library_and_special_case():
     assert np.abs(got0 - want0).max() < 1e-10
 
 
-# ---- MLP module (Sec. 2.3 last sentence; App. A.2.1 MLP table) --------------------------------
+# ---- MLP module (Sec. 2.3 last sentence; App. A.2.2 MLP table) --------------------------------
 def test_gelu_tanh_matches_library_and_closed_forms():
     x = np.linspace(-6.0, 6.0, 241)
     assert np.abs(mo.gelu_tanh(x) - F.gelu(t64(x), approximate="tanh").numpy()).max() < 1e-14

@@ -72,7 +72,7 @@ def test_ends_are_inclusive_and_errors():
 
 
 def test_window_fraction_of_the_papers_settings(golden_timestep_windows):
-    # Sec. 2.2 / App. A.2.2: broadcasting covers the stable middle of the run, roughly half to
+    # Sec. 2.2 / App. A.2.1: broadcasting covers the stable middle of the run, roughly half to
     # three quarters of the steps, never the first or the last one for these settings
     windows, _, _ = golden_timestep_windows
     for name, n_steps, first, stride, t_start, t_end, lo, hi in windows[:2]:
