@@ -29,10 +29,14 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
-# HBM bytes per launch of the dominant (spatial) kernel, from the rocprofv3 --pmc runs summarised in
+# HBM bytes per launch, from the rocprofv3 --pmc runs summarised in
 # profiles/attn_kernels_<workload>_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scales
-# a 1 GiB copy gives).  Not measured live: counters need the profiler.  None where no profile exists.
-PROFILED_SPATIAL_TRAFFIC_BYTES = {"opensora_480p": 416.1e6}
+# a 1 GiB copy gives), keyed by (workload, kind).  Not measured live: counters need the profiler.
+# None where no profile exists.
+PROFILED_TRAFFIC_BYTES = {("opensora_480p", 0): 416.1e6, ("opensora_480p", 1): 234.8e6, ("opensora_480p", 2): 122.1e6}
+SPATIAL_KERNEL = "attn_tile16_kernel (spatial)"
+CROSS_KERNEL = "attn_cross_kernel"
+OTHER_WORKLOADS = ("latte_512", "osp_512_long", "stress_720p")
 
 
 def parse():
@@ -49,6 +53,9 @@ def parse():
     ap.add_argument("--videos", type=int, default=1, help="timed videos when --steps is not given (steps = videos x the workload's steps)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--kind-reps", type=int, default=40, help="launches per kind in the per-kind section")
+    ap.add_argument("--repeats", type=int, default=5, help="repeats of the timed K-step region (PAB and no-PAB alternating); medians are reported")
+    ap.add_argument("--latency-videos", type=int, default=5, help="whole videos timed per schedule after one warm-up video")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the compact section on the other configurations")
     ap.add_argument("--profile-kind", default=None, choices=["spatial", "temporal", "cross"],
                     help="counter-collection mode: one 1 GiB device copy (calibration), then --kind-reps launches "
                          "of this kind over the rotating pool; prints no result line")
@@ -56,6 +63,172 @@ def parse():
                     help="profile mode only: multiply the inputs by this (0 = all-zero operands, the same "
                          "instruction stream with no data toggling: shows how far the clock follows the data)")
     return ap.parse_args()
+
+
+def _median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2]
+
+
+def _stats(xs, digits=4):
+    return {"median": round(_median(xs), digits), "min": round(min(xs), digits), "max": round(max(xs), digits), "n": len(xs)}
+
+
+class Harness:
+    """Device-resident synthetic inputs of one workload and the loops that play its denoising steps through
+    pab_attention.  Inputs rotate over a pool larger than the last-level cache; outputs go to the cache slots."""
+
+    def __init__(self, wl, dev, pool_n, input_scale=1.0):
+        import torch
+        from paper_2408_12588_amd import workloads as W
+        self.wl, self.dev, self.pool_n = wl, dev, pool_n
+        self.torch, self.W = torch, W
+        self.stream = torch.cuda.current_stream()
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(wl.seed)
+        self.full = (wl.T, wl.S, wl.heads, wl.head_dim)
+        dt = wl.torch_dtype
+
+        def randn(shape):
+            return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * input_scale).to(dt)
+
+        self.pool = [tuple(randn(self.full) for _ in range(3)) for _ in range(pool_n)]
+        if wl.peaked_frac > 0:
+            rows = torch.from_numpy(W.peaked_rows(wl)).to(dev)
+            for q, _, _ in self.pool:
+                q.view(wl.tokens, wl.heads, wl.head_dim)[rows] *= wl.peaked_scale
+        self.kv_cross = [tuple(randn((wl.L, wl.heads, wl.head_dim)) for _ in range(2)) for _ in range(pool_n)] \
+            if wl.intervals[W.CROSS] > 0 else None
+        self.calls = wl.calls_per_step()
+
+    def inputs(self, i, kind):
+        q, k, v = self.pool[i % self.pool_n]
+        if kind == self.W.CROSS:
+            k, v = self.kv_cross[i % self.pool_n]
+        return q, k, v
+
+    def run_steps(self, ctx, first_step, n, marks=None, events=None):
+        """Queue n denoising steps asynchronously; returns computed FLOPs and launches per kind.  marks collects one
+        stream event at the start of every video and one after the last step; events (a list per kind) collects
+        an event pair around every computed call."""
+        from paper_2408_12588_amd import pab
+        torch, wl = self.torch, self.wl
+        flops, launches = [0.0, 0.0, 0.0], [0, 0, 0]
+        i = first_step * len(self.calls)
+        for s in range(first_step, first_step + n):
+            step = s % wl.n_steps
+            if step == 0:
+                ctx.pab_reset()
+                if marks is not None:
+                    marks.append(torch.cuda.Event(enable_timing=True))
+                    marks[-1].record(self.stream)
+            for block, kind in self.calls:
+                q, k, v = self.inputs(i, kind)
+                i += 1
+                if events is not None and pab.pab_schedule(kind, step, wl.lo, wl.hi, ctx.cfg.interval[kind]) == pab.COMPUTE:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(self.stream)
+                    dec, _ = ctx.pab_attention(block, kind, step, q, k, v)
+                    e1.record(self.stream)
+                    events[kind].append((e0, e1))
+                else:
+                    dec, _ = ctx.pab_attention(block, kind, step, q, k, v)
+                if dec == pab.COMPUTE:
+                    flops[kind] += wl.flops(kind)
+                    launches[kind] += 1
+        if marks is not None:
+            marks.append(torch.cuda.Event(enable_timing=True))
+            marks[-1].record(self.stream)
+        return flops, launches
+
+    def region(self, ctx, n):
+        """n steps from step 0, bracketed by synchronisation: (seconds, flops per kind, launches per kind)."""
+        self.torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        flops, launches = self.run_steps(ctx, 0, n)
+        self.torch.cuda.synchronize()
+        return time.perf_counter() - t0, flops, launches
+
+    def videos(self, ctx, n_videos):
+        """Latencies (ms) of n whole videos played back to back, from stream events at the video boundaries."""
+        marks = []
+        self.run_steps(ctx, 0, n_videos * self.wl.n_steps, marks=marks)
+        self.torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:])]
+
+    def traced_video(self, ctx):
+        """One video with a stream-event pair around every computed call: per kind, the launch durations (ms) as
+        they are inside the loop, neighbours of other kinds in between and every output going to its own slot."""
+        events = [[], [], []]
+        self.run_steps(ctx, 0, self.wl.n_steps, events=events)
+        self.torch.cuda.synchronize()
+        return [[a.elapsed_time(b) for a, b in ev] for ev in events]
+
+    def back_to_back(self, ctx, kind, reps):
+        """reps launches of one kind in a row, inputs rotating over the pool, outputs over the cache slots."""
+        from paper_2408_12588_amd import pab
+        torch = self.torch
+        slots = [ctx.slot_tensor(b, kind) for b, k in self.calls if k == kind]
+        for i in range(3):
+            pab.pab_attention_compute(kind, *self.inputs(i, kind), out=slots[i % len(slots)])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(self.stream)
+        for i in range(reps):
+            pab.pab_attention_compute(kind, *self.inputs(i, kind), out=slots[i % len(slots)])
+        e1.record(self.stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+
+def kind_report(wl, kind, ms_list):
+    """Rates and roofline fractions of one kind from a list of launch durations (ms)."""
+    ms = sum(ms_list) / len(ms_list)
+    tf = wl.flops(kind) / (ms * 1e-3) / 1e12
+    gbs = wl.bytes(kind) / (ms * 1e-3) / 1e9
+    return {"avg_launch_ms": round(ms, 4), "min_launch_ms": round(min(ms_list), 4), "max_launch_ms": round(max(ms_list), 4),
+            "launches": len(ms_list), "tflops": round(tf, 2), "gbs": round(gbs, 1),
+            "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}
+
+
+def hbm_roofline(wl, kind, kernel, ms_list):
+    ms = sum(ms_list) / len(ms_list)
+    gbs = wl.bytes(kind) / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": kernel, "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": PROFILED_TRAFFIC_BYTES.get((wl.name, kind)),
+            "algorithmic_bytes": wl.bytes(kind), "avg_launch_ms": round(ms, 4), "launches": len(ms_list),
+            "where": "stream events around every computed call inside one video, outputs to the cache slots"}
+
+
+def other_workload(name, args, dev):
+    """One more configuration, compactly: a video with and without broadcasting, and the in-loop launch time of
+    every kind from one traced video."""
+    import torch
+    from paper_2408_12588_amd import pab, workloads as W
+    wl = W.BY_NAME[name]
+    h = Harness(wl, dev, min(args.pool, 4))
+    ctx = pab.PabContext(pab.config_of(wl), dev)
+    ctx0 = pab.PabContext(pab.config_of(wl, (1, 1, 1)), dev, workspace=ctx.workspace)
+    h.run_steps(ctx, 0, max(2, wl.lo + 1))                      # warm-up: a few steps
+    ms_pab = h.videos(ctx, 1)[0]
+    ms_all = h.videos(ctx0, 1)[0]
+    traced = h.traced_video(ctx)
+    flops = flops0 = 0.0
+    for kind in range(3):
+        if wl.intervals[kind] == 0:
+            continue
+        blocks = sum(1 for b, k in h.calls if k == kind)
+        computed = sum(pab.pab_schedule(kind, s, wl.lo, wl.hi, wl.intervals[kind]) == pab.COMPUTE for s in range(wl.n_steps))
+        flops += wl.flops(kind) * blocks * computed
+        flops0 += wl.flops(kind) * blocks * wl.n_steps
+    res = {"video_ms": {"pab": round(ms_pab, 3), "no_pab": round(ms_all, 3)},
+           "time_reduction": round(1.0 - ms_pab / ms_all, 4), "skipped_flop_fraction": round(1.0 - flops / flops0, 4),
+           "value_tflops": round(flops / (ms_pab * 1e-3) / 1e12, 2),
+           "kinds_in_loop": {W.KIND_NAMES[k]: kind_report(wl, k, traced[k]) for k in range(3) if traced[k]}}
+    ctx.pab_destroy()
+    ctx0.pab_destroy()
+    del h, ctx, ctx0
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -72,154 +245,85 @@ def main():
     Wm = args.warmup if args.warmup is not None else wl.n_steps
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    stream = torch.cuda.current_stream()
 
     # ---- inputs: seeded, on device, before any timing ----
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(wl.seed)
-    full = (wl.T, wl.S, wl.heads, wl.head_dim)
-    dt = wl.torch_dtype
+    h = Harness(wl, dev, args.pool, args.input_scale if args.profile_kind else 1.0)
 
-    def randn(shape):
-        return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(dt)
-
-    pool = [tuple(randn(full) for _ in range(3)) for _ in range(args.pool)]
-    if wl.peaked_frac > 0:
-        rows = torch.from_numpy(W.peaked_rows(wl)).to(dev)
-        for q, _, _ in pool:
-            q.view(wl.tokens, wl.heads, wl.head_dim)[rows] *= wl.peaked_scale
-    kv_cross = [tuple(randn((wl.L, wl.heads, wl.head_dim)) for _ in range(2)) for _ in range(args.pool)] \
-        if wl.intervals[W.CROSS] > 0 else None
-    calls = wl.calls_per_step()
-
-    def inputs(i, kind):
-        q, k, v = pool[i % args.pool]
-        if kind == W.CROSS:
-            k, v = kv_cross[i % args.pool]
-        return q, k, v
-
-    def run_steps(ctx, first_step, n, events=None, marks=None):
-        """Queue n denoising steps asynchronously; returns computed FLOPs per kind.  marks collects one
-        stream event at the start of every video and one after the last step."""
-        flops = [0.0, 0.0, 0.0]
-        launches = [0, 0, 0]
-        i = first_step * len(calls)
-        for s in range(first_step, first_step + n):
-            step = s % wl.n_steps
-            if step == 0:
-                ctx.pab_reset()
-                if marks is not None:
-                    marks.append(torch.cuda.Event(enable_timing=True))
-                    marks[-1].record(stream)
-            for block, kind in calls:
-                q, k, v = inputs(i, kind)
-                i += 1
-                if events is not None and kind == W.SPATIAL and \
-                        pab.pab_schedule(kind, step, wl.lo, wl.hi, ctx.cfg.interval[kind]) == pab.COMPUTE:
-                    e0 = torch.cuda.Event(enable_timing=True)
-                    e1 = torch.cuda.Event(enable_timing=True)
-                    e0.record(stream)
-                    dec, _ = ctx.pab_attention(block, kind, step, q, k, v)
-                    e1.record(stream)
-                    events.append((e0, e1))
-                else:
-                    dec, _ = ctx.pab_attention(block, kind, step, q, k, v)
-                if dec == pab.COMPUTE:
-                    flops[kind] += wl.flops(kind)
-                    launches[kind] += 1
-        if marks is not None:
-            marks.append(torch.cuda.Event(enable_timing=True))
-            marks[-1].record(stream)
-        return flops, launches
-
-    def timed(ctx, n, events=None, marks=None):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        flops, launches = run_steps(ctx, 0, n, events, marks)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0, flops, launches
-
-    def per_video_ms(marks, n):
-        """Latencies of the whole videos inside n timed steps (stream events at the video boundaries)."""
-        if n % wl.n_steps or len(marks) < 2:
-            return None
-        ms = [a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:])]
-        return {"per_video": [round(x, 3) for x in ms], "median": round(sorted(ms)[len(ms) // 2], 3)}
-
-    # ---- PAB schedule: warmup, then the timed region ----
     if args.profile_kind:
         kind = W.KIND_NAMES.index(args.profile_kind)
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)   # 1 GiB
         b = torch.empty_like(a)
         b.copy_(a)                                  # reads 1 GiB, writes 1 GiB: scale for FETCH_SIZE / WRITE_SIZE
-        out = torch.empty(full, device=dev, dtype=dt)
-        if args.input_scale != 1.0:
-            for ts in pool + (kv_cross or []):
-                for x in ts:
-                    x.mul_(args.input_scale)
+        outs = [torch.empty(h.full, device=dev, dtype=wl.torch_dtype) for _ in range(4)]
         for i in range(args.kind_reps):
-            pab.pab_attention_compute(kind, *inputs(i, kind), out=out)
+            pab.pab_attention_compute(kind, *h.inputs(i, kind), out=outs[i % 4])
         torch.cuda.synchronize()
         print("profiled %d launches of %s on %s" % (args.kind_reps, args.profile_kind, wl.name))
         return
 
+    # ---- the timed region: K steps under the PAB schedule and K steps with ranges 1/1/1 (the same library),
+    #      repeated and alternating, nothing but pab_attention calls inside ----
     ctx = pab.PabContext(pab.config_of(wl), dev)
-    run_steps(ctx, 0, Wm)
-    events, marks = [], []
-    sec, flops, launches = timed(ctx, K, events, marks)
-    spatial_ms = [a.elapsed_time(b) for a, b in events]
-    total_flops = sum(flops)
-    ctx.pab_destroy()
-
-    # ---- same library, broadcast ranges 1/1/1: the no-PAB baseline ----
     ctx0 = pab.PabContext(pab.config_of(wl, (1, 1, 1)), dev, workspace=ctx.workspace)
-    run_steps(ctx0, 0, min(Wm, 2))
-    marks0 = []
-    sec0, flops0, launches0 = timed(ctx0, K, None, marks0)
-    ctx0.pab_destroy()
+    h.run_steps(ctx, 0, Wm)
+    secs, secs0 = [], []
+    for _ in range(max(1, args.repeats)):
+        sec, flops, launches = h.region(ctx, K)
+        secs.append(sec)
+        sec0, flops0, launches0 = h.region(ctx0, K)
+        secs0.append(sec0)
+    sec, sec0 = _median(secs), _median(secs0)
+    total_flops = sum(flops)
 
-    # ---- per-kind section: back-to-back computes of one kind over the rotating pool ----
+    # ---- whole videos: one warm-up video, then --latency-videos timed ones, per schedule ----
+    vids = h.videos(ctx, 1 + args.latency_videos)[1:]
+    vids0 = h.videos(ctx0, 1 + args.latency_videos)[1:]
+
+    # ---- launch durations inside the loop: a separate traced video (events around every computed call) ----
+    traced = h.traced_video(ctx)
+    in_loop = {W.KIND_NAMES[k]: kind_report(wl, k, traced[k]) for k in range(3) if traced[k]}
+    sp = traced[W.SPATIAL]
+    if sp:
+        avg_ms = sum(sp) / len(sp)
+        achieved = wl.flops(W.SPATIAL) / (avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": SPATIAL_KERNEL, "achieved": round(achieved, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": PROFILED_TRAFFIC_BYTES.get((wl.name, W.SPATIAL)),
+                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
+                    "algorithmic_bytes": wl.bytes(W.SPATIAL), "avg_launch_ms": round(avg_ms, 4), "launches": len(sp),
+                    "flops_per_launch": wl.flops(W.SPATIAL),
+                    "where": "stream events around every computed spatial call inside one video"}
+    else:
+        roofline = None
+    roofline_hbm = {}
+    if traced[W.TEMPORAL]:
+        roofline_hbm["temporal"] = hbm_roofline(wl, W.TEMPORAL, "attn_temporal_kernel", traced[W.TEMPORAL])
+    if traced[W.CROSS]:
+        roofline_hbm["cross"] = hbm_roofline(wl, W.CROSS, CROSS_KERNEL, traced[W.CROSS])
+
+    # ---- per-kind section: back-to-back computes of one kind, inputs over the pool, outputs over the slots ----
     kinds = {}
-    out = torch.empty(full, device=dev, dtype=dt)
     for kind in (W.SPATIAL, W.TEMPORAL, W.CROSS):
         if wl.intervals[kind] == 0:
             continue
-        for i in range(3):
-            pab.pab_attention_compute(kind, *inputs(i, kind), out=out)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for i in range(args.kind_reps):
-            pab.pab_attention_compute(kind, *inputs(i, kind), out=out)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / args.kind_reps
+        ms = h.back_to_back(ctx, kind, args.kind_reps)
         tf = wl.flops(kind) / (ms * 1e-3) / 1e12
         gbs = wl.bytes(kind) / (ms * 1e-3) / 1e9
         kinds[W.KIND_NAMES[kind]] = {
             "ms_per_call": round(ms, 4), "tflops": round(tf, 2), "gbs": round(gbs, 1),
             "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}
-
-    # ---- roofline of the dominant kernel (spatial attention), from events inside the timed region ----
-    if spatial_ms:
-        avg_ms = sum(spatial_ms) / len(spatial_ms)
-        achieved = wl.flops(W.SPATIAL) / (avg_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "attn_tile16_kernel (spatial)", "achieved": round(achieved, 2),
-                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": PROFILED_SPATIAL_TRAFFIC_BYTES.get(wl.name),
-                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
-                    "algorithmic_bytes": wl.bytes(W.SPATIAL), "avg_launch_ms": round(avg_ms, 4), "launches": len(spatial_ms),
-                    "flops_per_launch": wl.flops(W.SPATIAL)}
-    else:
-        roofline = None
+    ctx.pab_destroy()
+    ctx0.pab_destroy()
 
     # ---- schedule accounting ----
     skipped_flop_fraction = 1.0 - total_flops / sum(flops0) if sum(flops0) else 0.0
     time_reduction = 1.0 - sec / sec0
-    # what the per-kind kernel times predict (reuse is free, so a kind's time scales with its launches)
-    ms_of = [kinds.get(n, {}).get("ms_per_call", 0.0) for n in W.KIND_NAMES]
+    # what the in-loop launch times predict (reuse is free, so a kind's time scales with its launches)
+    ms_of = [in_loop.get(n, {}).get("avg_launch_ms", 0.0) for n in W.KIND_NAMES]
     t_pab = sum(l * m for l, m in zip(launches, ms_of))
     t_all = sum(l * m for l, m in zip(launches0, ms_of))
     time_weighted_prediction = 1.0 - t_pab / t_all if t_all else 0.0
+    vid_red = 1.0 - _median(vids) / _median(vids0)
 
     result = {
         "metric": "attention TFLOP/s + %roofline; per-video attention latency PAB vs no-PAB",
@@ -232,10 +336,16 @@ def main():
         "config": {"workload": wl.name, "blocks": wl.n_blocks, "T": wl.T, "S": wl.S, "L": wl.L,
                    "heads": wl.heads, "head_dim": wl.head_dim, "video_steps": wl.n_steps,
                    "intervals": list(wl.intervals), "window": [wl.lo, wl.hi], "input_pool": args.pool},
-        "value_definition": "attention FLOPs actually computed under the PAB schedule / wall time of the timed steps",
+        "value_definition": "attention FLOPs actually computed under the PAB schedule in K steps / median wall time of "
+                            "the K-step region over the repeats",
+        "timed_region": {"repeats": len(secs), "pab_ms": _stats([x * 1e3 for x in secs], 3),
+                         "no_pab_ms": _stats([x * 1e3 for x in secs0], 3)},
         "roofline": roofline,
+        "roofline_hbm": roofline_hbm,
         "latency_ms": {"pab": round(sec * 1e3, 3), "no_pab": round(sec0 * 1e3, 3), "steps": K,
-                       "videos_pab": per_video_ms(marks, K), "videos_no_pab": per_video_ms(marks0, K)},
+                       "videos_pab": {"per_video": [round(x, 3) for x in vids], **_stats(vids, 3)},
+                       "videos_no_pab": {"per_video": [round(x, 3) for x in vids0], **_stats(vids0, 3)},
+                       "video_time_reduction": round(vid_red, 4)},
         "pab": {"time_reduction": round(time_reduction, 4), "skipped_flop_fraction": round(skipped_flop_fraction, 4),
                 "gap_abs": round(time_reduction - skipped_flop_fraction, 4),
                 "gap_rel": round((time_reduction - skipped_flop_fraction) / skipped_flop_fraction, 4) if skipped_flop_fraction else None,
@@ -243,12 +353,18 @@ def main():
                 "skipped_launch_fraction": [round(1.0 - a / b, 4) if b else None for a, b in zip(launches, launches0)],
                 "launches_pab": launches, "launches_no_pab": launches0,
                 "effective_tflops": round(sum(flops0) / sec / 1e12, 3)},
+        "kinds_in_loop": in_loop,
         "kinds": kinds,
     }
+    if not args.no_workloads:
+        del h
+        torch.cuda.empty_cache()
+        result["workloads"] = {n: other_workload(n, args, dev) for n in OTHER_WORKLOADS if n != wl.name}
+        h = Harness(wl, dev, args.pool)
     if not args.no_mfma_reference and wl.dtype == "bf16":
         result["mfma_reference"] = mfma_reference(dev)
     if not args.no_module and wl.dtype == "bf16":
-        result["module"] = module_section(wl, pool, args, dev)
+        result["module"] = module_section(wl, h.pool, args, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     print(json.dumps(result), flush=True)

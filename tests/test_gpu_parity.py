@@ -223,9 +223,10 @@ def test_tiny_video_every_cell(pab):
     with pytest.raises(pab.PabError) as e:       # reuse step first after reset: nothing cached
         ctx.pab_attention(0, W.SPATIAL, 3, None, None, None)
     assert e.value.status == pab.ESTATE
-    dec, _ = ctx.pab_attention(0, W.SPATIAL, 0, q, k, v)
-    assert dec == pab.COMPUTE
-    dec, _ = ctx.pab_attention(0, W.SPATIAL, 3, None, None, None)   # window step 3 reuses; NULL inputs are fine
+    for step in (0, 1, 2):
+        dec, _ = ctx.pab_attention(0, W.SPATIAL, step, q, k, v)
+        assert dec == pab.COMPUTE
+    dec, _ = ctx.pab_attention(0, W.SPATIAL, 3, None, None, None)   # window step 3 reuses step 2; NULL inputs are fine
     assert dec == pab.REUSE
     torch.cuda.synchronize()
     ctx.pab_destroy()
