@@ -29,11 +29,14 @@
 // m is only raised when some lane's scores exceed it by more than 8 in the exponent
 // (probabilities then stay below 2^8, harmless in fp32 / bf16), and only then do the four lanes
 // exchange their tile maxima.  Numerator and denominator always share the same m, so the quotient
-// is unaffected.
+// is unaffected.  m + margin and -m c are kept beside m (they change only when m does), so the test
+// and the exponent's offset cost no arithmetic of their own per tile.
 //
 // Measured no faster: software pipelining inside the wavefront (scores of tile t + 1 issued
 // before the exponentials of tile t), 64 queries per wavefront, wave priorities around the
-// matrix or the exponential phases.
+// matrix or the exponential phases, O^T accumulators in the AGPR half of the register file,
+// 10 or 16 wavefronts per workgroup, splitting the ragged last query block of a sequence over
+// key groups that combine through LDS.
 #pragma once
 #include <type_traits>
 #include "mfma_util.hpp"
@@ -196,10 +199,12 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the q loads outside the loop (the staging loads are invisible to the compiler)
 
   f32x4 oacc[DT16][2];
-  float m_run[2];
+  float m_run[2], m_thr[2], m_negc[2];   // running maximum, m + margin, -m c: the last two change only when m does
 #pragma unroll
   for (int qh = 0; qh < 2; ++qh) {
     m_run[qh] = -INFINITY;
+    m_thr[qh] = -INFINITY;
+    m_negc[qh] = 0.0f;
 #pragma unroll
     for (int dt = 0; dt < DT16; ++dt)
 #pragma unroll
@@ -272,11 +277,12 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
     float mx[2];
     bool grow = false;
 #pragma unroll
-    for (int qh = 0; qh < 2; ++qh) {
-      const float a = fmaxf(fmaxf(S[0][qh][0], S[0][qh][1]), fmaxf(S[0][qh][2], S[0][qh][3]));
-      const float b = fmaxf(fmaxf(S[1][qh][0], S[1][qh][1]), fmaxf(S[1][qh][2], S[1][qh][3]));
-      mx[qh] = fmaxf(a, b);
-      grow |= mx[qh] > m_run[qh] + thr;
+    for (int qh = 0; qh < 2; ++qh) {   // a chain of three-operand maxima: 3 + 1 instructions for the 8 scores
+      float a = fmaxf(fmaxf(S[0][qh][0], S[0][qh][1]), S[0][qh][2]);
+      a = fmaxf(fmaxf(a, S[0][qh][3]), S[1][qh][0]);
+      a = fmaxf(fmaxf(a, S[1][qh][1]), S[1][qh][2]);
+      mx[qh] = fmaxf(a, S[1][qh][3]);
+      grow |= mx[qh] > m_thr[qh];
     }
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {   // rare after the first tile
 #pragma unroll
@@ -286,6 +292,8 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
         const float m_new = fmaxf(m_run[qh], full);
         const float alpha = __builtin_amdgcn_exp2f((m_run[qh] - m_new) * c);
         m_run[qh] = m_new;
+        m_thr[qh] = m_new + thr;
+        m_negc[qh] = -m_new * c;
 #pragma unroll
         for (int dt = 0; dt < DT16; ++dt)
 #pragma unroll
@@ -297,12 +305,11 @@ __global__ __launch_bounds__(64 * NWV, MINW) void attn_tile16_kernel(const TileP
     bf16x8 pf[2];
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
-      const float mc = m_run[qh] * c;
 #pragma unroll
       for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          pf[qh][4 * kh + r] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(S[kh][qh][r], c, -mc));
+          pf[qh][4 * kh + r] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(S[kh][qh][r], c, m_negc[qh]));
     }
 
     // ---- O^T += V^T P^T: 16 rows of V^T over all 32 keys per instruction ----

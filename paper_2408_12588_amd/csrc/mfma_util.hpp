@@ -104,10 +104,12 @@ __device__ __forceinline__ bf16x8 splat8(float x) {
 // (s_waitcnt vmcnt) before the barrier that publishes the data.
 __device__ __forceinline__ void dma16_to_lds(const void *base, unsigned voff, unsigned lds_addr) {
   lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);   // uniform by contract; tell the compiler
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+  // The LDS address travels in M0.  It is bound to that register as an operand, so the compiler writes M0 itself and
+  // knows that this statement reads it; the s_nop is the wait state between a write of M0 and the instruction using it.
+  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
-               : "v"(voff), "s"(base), "s"(lds_addr)
-               : "memory", "m0");
+               : "v"(voff), "s"(base), "{m0}"(lds_addr)
+               : "memory");
 }
 
 __device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
