@@ -38,8 +38,9 @@ size_t elem_size(int dtype) { return dtype == PAB_BF16 ? 2 : 4; }
 // ---- launches -----------------------------------------------------------------
 
 constexpr int TILE_NWV = 8;    // wavefronts per workgroup: 256 queries share each staged K/V tile (4: 1.5-2% slower)
-constexpr int TILE_NST = 4;    // LDS ring stages (one 32-key tile each)
 constexpr int TILE_MINW = 4;   // wavefronts per SIMD the register budget is sized for
+constexpr int TILE_SPLIT_G = 4;   // key groups of a split item
+constexpr int TILE_SLOTS = 512;   // workgroups the chip holds at once: 2 per CU (16 wavefronts) x 256 CUs
 
 template <typename T, int D>
 int launch_tile(int n_batch, int n_head, int sq, int sk, long long q_bs, long long q_ss, long long kv_bs,
@@ -51,14 +52,29 @@ int launch_tile(int n_batch, int n_head, int sq, int sk, long long q_bs, long lo
   p.o_bs = q_bs; p.o_ss = q_ss;
   p.c = (float)(1.4426950408889634 / std::sqrt((double)D));
   constexpr int QBLK = 32 * TILE_NWV;
-  p.n_qblk = (sq + QBLK - 1) / QBLK;
-  // staging addresses a 32-key tile with 32-bit byte offsets
-  if (32 * kv_ss * (long long)sizeof(T) >= (1LL << 32)) return fail(PAB_EINVAL, "sequence stride too large");
+  p.n_item = (sq + QBLK - 1) / QBLK;
+  // staging addresses the key tiles of one step with 32-bit byte offsets
+  if (32 * TILE_SPLIT_G * kv_ss * (long long)sizeof(T) >= (1LL << 32)) return fail(PAB_EINVAL, "sequence stride too large");
   const long long n_bh = (long long)n_batch * n_head;
-  const long long grid = (n_bh + 7) / 8 * 8 * p.n_qblk;
+  if (n_bh > 0x3fffffffLL) return fail(PAB_EINVAL, "problem too large for one launch");
+  // Workgroups all take about the same time, so a launch runs in rounds of TILE_SLOTS.  When the last round
+  // would be at most a quarter full, the (batch, head) problems it would hold are done as split items
+  // instead (a quarter of the queries, four key groups each): four times the workgroups, a quarter of the steps.
+  p.bh_plain = (int)n_bh;
+  p.n_split = 0;
+  p.split_g = TILE_SPLIT_G;
+  const long long total = n_bh * p.n_item, rest = total % TILE_SLOTS;
+  const int ntile = (sk + 31) / 32;
+  if (total > TILE_SLOTS && rest >= p.n_item && rest * 4 <= TILE_SLOTS && ntile >= 4 * TILE_SPLIT_G) {
+    p.bh_plain = (int)(n_bh - rest / p.n_item);
+    p.n_split = (sq + QBLK / TILE_SPLIT_G - 1) / (QBLK / TILE_SPLIT_G);
+  }
+  const long long plain_wgs = (long long)(p.bh_plain + 7) / 8 * 8 * p.n_item;
+  const long long grid = plain_wgs + (n_bh - p.bh_plain + 7) / 8 * 8 * p.n_split;
   if (grid > 0x7fffffffLL) return fail(PAB_EINVAL, "problem too large for one launch (%lld workgroups)", grid);
+  p.plain_wgs = (int)plain_wgs;
   constexpr bool DIRECT = sizeof(T) == 2;   // bf16 rows go from global memory straight into LDS
-  hipLaunchKernelGGL((pab::attn_tile16_kernel<T, D, TILE_NWV, TILE_NST, TILE_MINW, DIRECT>), dim3((unsigned)grid),
+  hipLaunchKernelGGL((pab::attn_tile16_kernel<T, D, TILE_NWV, TILE_MINW, DIRECT>), dim3((unsigned)grid),
                      dim3(64 * TILE_NWV), 0, st, p);
   return PAB_OK;
 }

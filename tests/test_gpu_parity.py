@@ -49,6 +49,9 @@ SHAPES = [
     (W.SPATIAL, 2, 200, 0, 2, 32, "bf16"),
     (W.SPATIAL, 2, 130, 0, 2, 72, "f32"),
     (W.SPATIAL, 4, 64, 0, 4, 32, "f32"),       # the Tiny configuration's spatial call
+    (W.SPATIAL, 1, 512, 0, 260, 72, "bf16"),   # 520 workgroups: the 8 past a full round become split items (4 key groups, combined in LDS)
+    (W.SPATIAL, 1, 700, 0, 261, 72, "bf16"),   # ... with a ragged last query block and a ragged last key tile in every key group
+    (W.SPATIAL, 1, 520, 0, 264, 32, "f32"),    # ... head dim 32, fp32 rows (staged through registers)
     (W.TEMPORAL, 16, 50, 0, 4, 72, "bf16"),
     (W.TEMPORAL, 17, 37, 0, 3, 72, "bf16"),    # 17 frames: second 16-key half almost empty
     (W.TEMPORAL, 1, 9, 0, 2, 72, "bf16"),      # one frame: identity on V
