@@ -7,7 +7,8 @@
 // rows into LDS once (direct global -> LDS loads, row-major as in memory), and
 // then every wavefront walks over 32-query tiles of the head on its own, with
 // no further synchronisation.  Per query tile it keeps the q operands in
-// registers and runs the online softmax of the tile kernel (attn_tile16.hpp:
+// registers (those of its next tile are requested before the current one is
+// computed) and runs the online softmax of the tile kernel (attn_tile16.hpp:
 // 16 x 16 x 32 MFMA sub-tiles, the same lane layouts) over the key tiles:
 //   S^T = K Q^T  ->  running max (raised lazily)  ->  P^T = exp2(c (S^T - m))
 //   ->  O^T += V^T P^T, the softmax denominator riding along as row D of O^T
@@ -77,6 +78,48 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
   const int ntile = (L + 31) >> 5;          // key tiles in use (<= LTMAX, checked by the host)
   const int rows = 32 * ntile;
 
+  const float c = p.c;
+  const float thr = 8.0f / c;   // raise the running maximum only past this margin (raw score units)
+  constexpr int REM = D % 32;
+  constexpr bool REM16 = REM > 0 && REM <= 16;   // the last columns of the first product as one 16-column step
+  constexpr int KS = REM16 ? D / 32 : (D + 31) / 32;
+  constexpr int DT16 = (D + 1 + 15) / 16;        // 16-row tiles of O^T incl. the row of the denominator
+  const int k_off = l16 * RP + 8 * (g4 ^ k_swizzle<D>(l16));        // + (32 kt + 16 kh) * RP + 32 ks
+  const int kr_off = l16 * RP + 32 * KS + 4 * g4;                   // + (32 kt + 16 kh) * RP
+  const int v_off = (4 * g4 + (l16 >> 2)) * VP + 4 * (l16 & 3);     // + 32 kt * VP, + 16 * VP for the second key half, + 16 dt
+
+  const int stride = parts * NW;
+  // q operands (B) of a tile: query 16 qh + l16, columns 32 ks + 8 g4; tail rows load a valid row, never stored.
+  // The rows of the next tile are requested before the current one is computed and arrive meanwhile.
+  bf16x8 qf[2][KS], qn[2][KS];
+  bf16x4 qr[2], qrn[2];
+  auto request_q = [&](int t) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qh2 = 0; qh2 < 2; ++qh2) {
+      int qrow = 32 * t + 16 * qh2 + l16;
+      qrow = qrow < n_tok ? qrow : n_tok - 1;
+      const T *qp = qh + (long long)qrow * row;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int d0 = 32 * ks + 8 * g4;
+        qn[qh2][ks] = (d0 < D) ? Io<T>::load8(qp + d0) : zero8();
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) qrn[qh2][e] = (bf16_t)0.0f;
+      if (REM16 && 32 * KS + 4 * g4 < D) qrn[qh2] = Io<T>::load4(qp + 32 * KS + 4 * g4);
+    }
+  };
+  auto take_q = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int qh2 = 0; qh2 < 2; ++qh2) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) qf[qh2][ks] = qn[qh2][ks];
+      qr[qh2] = qrn[qh2];
+    }
+  };
+  int t = t_lo + part * NW + wave;
+  if (t < t_hi) request_q(t);   // in flight while K and V are staged
+
   // ---- K and V of the head, 64-chunk rounds dealt round-robin to the wavefronts.  Slots that no
   //      load fills (V rows past L, the constant chunks) are written as ordinary LDS stores. ----
   const int kr = (rows * CH + 63) >> 6, vr = (rows * VCH + 63) >> 6;
@@ -105,44 +148,22 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
   // The 16-column operand read of the last K row runs 8 elements past it when D is not a multiple
   // of 16; what it finds there meets zero q columns, but has to be finite.
   if (rows < LP && tid < 4) reinterpret_cast<unsigned *>(Ks + rows * RP)[tid] = 0u;
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // this wavefront's share of K and V has landed
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // this wavefront's share of K and V has landed (and its first q rows)
   __syncthreads();                      // ... everyone's
+  if (t >= t_hi) return;
 
-  const float c = p.c;
-  const float thr = 8.0f / c;   // raise the running maximum only past this margin (raw score units)
-  constexpr int REM = D % 32;
-  constexpr bool REM16 = REM > 0 && REM <= 16;   // the last columns of the first product as one 16-column step
-  constexpr int KS = REM16 ? D / 32 : (D + 31) / 32;
-  constexpr int DT16 = (D + 1 + 15) / 16;        // 16-row tiles of O^T incl. the row of the denominator
-  const int k_off = l16 * RP + 8 * (g4 ^ k_swizzle<D>(l16));        // + (32 kt + 16 kh) * RP + 32 ks
-  const int kr_off = l16 * RP + 32 * KS + 4 * g4;                   // + (32 kt + 16 kh) * RP
-  const int v_off = (4 * g4 + (l16 >> 2)) * VP + 4 * (l16 & 3);     // + 32 kt * VP, + 16 * VP for the second key half, + 16 dt
-
-  const int stride = parts * NW;
-  for (int t = t_lo + part * NW + wave; t < t_hi; t += stride) {
-    // ---- q operands (B): query 16 qh + l16, columns 32 ks + 8 g4; tail rows load a valid row, never stored ----
-    bf16x8 qf[2][KS];
-    bf16x4 qr[2];
-#pragma unroll
-    for (int qh2 = 0; qh2 < 2; ++qh2) {
-      int qrow = 32 * t + 16 * qh2 + l16;
-      qrow = qrow < n_tok ? qrow : n_tok - 1;
-      const T *qp = qh + (long long)qrow * row;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int d0 = 32 * ks + 8 * g4;
-        qf[qh2][ks] = (d0 < D) ? Io<T>::load8(qp + d0) : zero8();
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) qr[qh2][e] = (bf16_t)0.0f;
-      if (REM16 && 32 * KS + 4 * g4 < D) qr[qh2] = Io<T>::load4(qp + 32 * KS + 4 * g4);
-    }
+  for (;;) {
+    take_q();
+    const bool more = t + stride < t_hi;
+    if (more) request_q(t + stride);
 
     f32x4 oacc[DT16][2];
-    float m_run[2];
+    float m_run[2], m_thr[2], m_negc[2];   // running maximum, m + margin, -m c: the last two change only when m does
 #pragma unroll
     for (int qh2 = 0; qh2 < 2; ++qh2) {
       m_run[qh2] = -INFINITY;
+      m_thr[qh2] = -INFINITY;
+      m_negc[qh2] = 0.0f;
 #pragma unroll
       for (int dt = 0; dt < DT16; ++dt)
 #pragma unroll
@@ -183,11 +204,12 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
       float mx[2];
       bool grow = false;
 #pragma unroll
-      for (int qh2 = 0; qh2 < 2; ++qh2) {
-        const float a = fmaxf(fmaxf(S[0][qh2][0], S[0][qh2][1]), fmaxf(S[0][qh2][2], S[0][qh2][3]));
-        const float b2 = fmaxf(fmaxf(S[1][qh2][0], S[1][qh2][1]), fmaxf(S[1][qh2][2], S[1][qh2][3]));
-        mx[qh2] = fmaxf(a, b2);
-        grow |= mx[qh2] > m_run[qh2] + thr;
+      for (int qh2 = 0; qh2 < 2; ++qh2) {   // a chain of three-operand maxima over the lane's 8 scores
+        float a = fmaxf(fmaxf(S[0][qh2][0], S[0][qh2][1]), S[0][qh2][2]);
+        a = fmaxf(fmaxf(a, S[0][qh2][3]), S[1][qh2][0]);
+        a = fmaxf(fmaxf(a, S[1][qh2][1]), S[1][qh2][2]);
+        mx[qh2] = fmaxf(a, S[1][qh2][3]);
+        grow |= mx[qh2] > m_thr[qh2];
       }
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {   // rare after the first tile
 #pragma unroll
@@ -197,6 +219,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
           const float m_new = fmaxf(m_run[qh2], full);
           const float alpha = __builtin_amdgcn_exp2f((m_run[qh2] - m_new) * c);
           m_run[qh2] = m_new;
+          m_thr[qh2] = m_new + thr;
+          m_negc[qh2] = -m_new * c;
 #pragma unroll
           for (int dt = 0; dt < DT16; ++dt)
 #pragma unroll
@@ -207,14 +231,12 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
       // P^T = exp2(c S^T - c m): the lane's keys of the first half, then of the second, are its B operand
       bf16x8 pf[2];
 #pragma unroll
-      for (int qh2 = 0; qh2 < 2; ++qh2) {
-        const float mc = m_run[qh2] * c;
+      for (int qh2 = 0; qh2 < 2; ++qh2)
 #pragma unroll
         for (int kh2 = 0; kh2 < 2; ++kh2)
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            pf[qh2][4 * kh2 + r] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(S[kh2][qh2][r], c, -mc));
-      }
+            pf[qh2][4 * kh2 + r] = (bf16_t)__builtin_amdgcn_exp2f(__builtin_fmaf(S[kh2][qh2][r], c, m_negc[qh2]));
       // O^T += V^T P^T
 #pragma unroll
       for (int dt = 0; dt < DT16; ++dt) {
@@ -245,6 +267,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void attn_cross_long_kernel(const Cr
         }
       }
     }
+    if (!more) break;
+    t += stride;
   }
 }
 
