@@ -69,6 +69,11 @@ typedef struct pab_config {
   int n_steps;    /* diffusion steps of the run */
   int interval[3];
   int range_lo, range_hi;
+  /* Optional, n_blocks entries or NULL: bit k of block_kinds[b] set = block b has attention of kind k.
+   * Models whose blocks alternate (one spatial, the next temporal) get one cache slot per block this way
+   * instead of one per kind and block.  NULL = every block has every kind with interval > 0.  A set bit
+   * for a kind with interval 0 is PAB_EINVAL.  Host memory, read during the call only. */
+  const unsigned char *block_kinds;
 } pab_config;
 
 typedef struct pab_ctx pab_ctx;
@@ -120,7 +125,8 @@ int pab_preset(int model, int level, int interval[3], double *t_start, double *t
 
 /*
  * Bytes of device memory the broadcast cache of `cfg` needs: one output tensor
- * [T, S, H, D] per (block, present kind), each slot rounded up to 256 bytes.
+ * [T, S, H, D] per (block, kind that the block has), each slot rounded up to 256
+ * bytes, laid out block-major, kind-minor.
  * Returns 0 if cfg is NULL or invalid (pab_last_error says why).
  */
 size_t pab_workspace_bytes(const pab_config *cfg);
@@ -346,7 +352,7 @@ int pab_mlp_destroy(pab_mlp_ctx *ctx);
  * ctx is NULL. */
 long long pab_launch_count(const pab_ctx *ctx);
 
-/* Device pointer of slot (block, kind) without touching any state, or NULL. */
+/* Device pointer of slot (block, kind) without touching any state; NULL if the block has no such kind. */
 const void *pab_slot_ptr(const pab_ctx *ctx, int block, int kind);
 
 /* Free the host-side context (the workspace stays the caller's). */

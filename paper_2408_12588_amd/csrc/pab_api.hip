@@ -222,18 +222,32 @@ int check_config(const pab_config *c) {
   if (!present) return fail(PAB_EINVAL, "no attention kind present (all intervals 0)");
   if (c->range_lo < 0 || c->range_lo > c->range_hi)
     return fail(PAB_EINVAL, "window [%d, %d] must satisfy 0 <= lo <= hi", c->range_lo, c->range_hi);
+  if (c->block_kinds)
+    for (int b = 0; b < c->n_blocks; ++b) {
+      if (c->block_kinds[b] > 7) return fail(PAB_EINVAL, "block_kinds[%d]=%d has bits beyond the three kinds", b, c->block_kinds[b]);
+      for (int k = 0; k < 3; ++k)
+        if (((c->block_kinds[b] >> k) & 1) && c->interval[k] == 0)
+          return fail(PAB_EINVAL, "block_kinds[%d] names kind %d, which has interval 0", b, k);
+    }
   const int kind_for_shape = c->interval[PAB_CROSS] > 0 ? PAB_CROSS : PAB_SPATIAL;
   return check_shape(kind_for_shape, c->dtype, c->T, c->S, c->L, c->heads, c->head_dim);
+}
+
+// kinds that block b has: the caller's mask, else every kind with a broadcast range
+unsigned kinds_of_block(const pab_config &c, int b) {
+  if (c.block_kinds) return c.block_kinds[b];
+  unsigned m = 0;
+  for (int k = 0; k < 3; ++k) m |= (unsigned)(c.interval[k] > 0) << k;
+  return m;
 }
 
 }  // namespace
 
 struct pab_ctx {
-  pab_config cfg;
+  pab_config cfg;        // block_kinds is NULL here: the mask is copied into slot_index
   unsigned char *workspace;
   size_t slot_bytes;
-  int slot_of_kind[3];   // index of the kind among the present kinds, -1 if absent
-  int n_present;
+  std::vector<long long> slot_index;   // per (block, kind): slot number in the slab (block-major, kind-minor), -1 if absent
   std::vector<int> last_step;      // per (block, kind): last step seen since reset, -1 if none
   std::vector<int> computed_step;  // per (block, kind): step whose output the slot holds, -1 if none
   long long launches;
@@ -248,6 +262,8 @@ int schedule_cell(pab_ctx *ctx, int block, int kind, int step, void **slot) {
   if (!kind_ok(kind)) return fail(PAB_EINVAL, "kind %d is not spatial(0)/temporal(1)/cross(2)", kind);
   if (c.interval[kind] == 0) return fail(PAB_EINVAL, "kind %d is absent from this config (interval 0)", kind);
   if (block < 0 || block >= c.n_blocks) return fail(PAB_EINVAL, "block %d outside [0, %d)", block, c.n_blocks);
+  if (ctx->slot_index[(size_t)block * 3 + kind] < 0)
+    return fail(PAB_EINVAL, "block %d has no attention of kind %d (block_kinds)", block, kind);
   if (step < 0 || step >= c.n_steps) return fail(PAB_EINVAL, "step %d outside [0, %d)", step, c.n_steps);
   const size_t cell = (size_t)block * 3 + kind;
   if (step < ctx->last_step[cell])
@@ -647,9 +663,9 @@ int pab_preset(int model, int level, int interval[3], double *t_start, double *t
 
 size_t pab_workspace_bytes(const pab_config *cfg) {
   if (check_config(cfg) != PAB_OK) return 0;
-  int present = 0;
-  for (int k = 0; k < 3; ++k) present += cfg->interval[k] > 0;
-  return slot_bytes_of(*cfg) * (size_t)present * (size_t)cfg->n_blocks;
+  size_t slots = 0;
+  for (int b = 0; b < cfg->n_blocks; ++b) slots += (size_t)__builtin_popcount(kinds_of_block(*cfg, b));
+  return slot_bytes_of(*cfg) * slots;
 }
 
 int pab_create(const pab_config *cfg, void *workspace, size_t workspace_bytes, pab_ctx **out) {
@@ -667,8 +683,12 @@ int pab_create(const pab_config *cfg, void *workspace, size_t workspace_bytes, p
   ctx->cfg = *cfg;
   ctx->workspace = static_cast<unsigned char *>(workspace);
   ctx->slot_bytes = slot_bytes_of(*cfg);
-  ctx->n_present = 0;
-  for (int k = 0; k < 3; ++k) ctx->slot_of_kind[k] = cfg->interval[k] > 0 ? ctx->n_present++ : -1;
+  ctx->slot_index.assign((size_t)cfg->n_blocks * 3, -1);
+  long long next = 0;
+  for (int b = 0; b < cfg->n_blocks; ++b)
+    for (int k = 0; k < 3; ++k)
+      if ((kinds_of_block(*cfg, b) >> k) & 1) ctx->slot_index[(size_t)b * 3 + k] = next++;
+  ctx->cfg.block_kinds = nullptr;   // the caller's array is not kept
   ctx->last_step.assign((size_t)cfg->n_blocks * 3, -1);
   ctx->computed_step.assign((size_t)cfg->n_blocks * 3, -1);
   ctx->launches = 0;
@@ -685,8 +705,9 @@ int pab_reset(pab_ctx *ctx) {
 }
 
 const void *pab_slot_ptr(const pab_ctx *ctx, int block, int kind) {
-  if (!ctx || !kind_ok(kind) || block < 0 || block >= ctx->cfg.n_blocks || ctx->slot_of_kind[kind] < 0) return nullptr;
-  return ctx->workspace + ((size_t)block * ctx->n_present + ctx->slot_of_kind[kind]) * ctx->slot_bytes;
+  if (!ctx || !kind_ok(kind) || block < 0 || block >= ctx->cfg.n_blocks) return nullptr;
+  const long long slot = ctx->slot_index[(size_t)block * 3 + kind];
+  return slot < 0 ? nullptr : ctx->workspace + (size_t)slot * ctx->slot_bytes;
 }
 
 int pab_attention(pab_ctx *ctx, int block, int kind, int step, const void *q, const void *k, const void *v,

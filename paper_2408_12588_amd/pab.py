@@ -41,7 +41,8 @@ class pab_config(ctypes.Structure):
     _fields_ = [("n_blocks", ctypes.c_int), ("T", ctypes.c_int), ("S", ctypes.c_int), ("L", ctypes.c_int),
                 ("heads", ctypes.c_int), ("head_dim", ctypes.c_int), ("dtype", ctypes.c_int),
                 ("n_steps", ctypes.c_int), ("interval", ctypes.c_int * 3),
-                ("range_lo", ctypes.c_int), ("range_hi", ctypes.c_int)]
+                ("range_lo", ctypes.c_int), ("range_hi", ctypes.c_int),
+                ("block_kinds", ctypes.POINTER(ctypes.c_ubyte))]
 
 
 class pab_module_weights(ctypes.Structure):
@@ -171,9 +172,18 @@ def pab_preset(model: int, level: int):
     return tuple(iv), a.value, b.value
 
 
-def make_config(n_blocks, T, S, L, heads, head_dim, dtype, n_steps, interval, range_lo, range_hi) -> pab_config:
-    return pab_config(n_blocks, T, S, L, heads, head_dim, dtype, n_steps, (ctypes.c_int * 3)(*interval),
-                      range_lo, range_hi)
+def make_config(n_blocks, T, S, L, heads, head_dim, dtype, n_steps, interval, range_lo, range_hi,
+                block_kinds=None) -> pab_config:
+    """``block_kinds``: optional sequence of n_blocks bit masks (bit k = the block has attention of kind k)."""
+    cfg = pab_config(n_blocks, T, S, L, heads, head_dim, dtype, n_steps, (ctypes.c_int * 3)(*interval),
+                     range_lo, range_hi, None)
+    if block_kinds is not None:
+        if len(block_kinds) != n_blocks:
+            raise ValueError("block_kinds needs one entry per block")
+        mask = (ctypes.c_ubyte * n_blocks)(*block_kinds)
+        cfg.block_kinds = ctypes.cast(mask, ctypes.POINTER(ctypes.c_ubyte))
+        cfg._mask = mask   # keeps the array alive as long as the struct
+    return cfg
 
 
 def config_of(wl, intervals=None) -> pab_config:
@@ -181,8 +191,11 @@ def config_of(wl, intervals=None) -> pab_config:
     e.g. (1, 1, 1) masked to the present kinds for the no-broadcast baseline)."""
     iv = tuple(wl.intervals if intervals is None else intervals)
     iv = tuple(i if w > 0 else 0 for i, w in zip(iv, wl.intervals))
+    mask = None
+    if wl.alternating:   # blocks that hold one kind each get one slot each
+        mask = [sum(1 << k for k in wl.kinds_of_block(b)) for b in range(wl.n_blocks)]
     return make_config(wl.n_blocks, wl.T, wl.S, wl.L, wl.heads, wl.head_dim,
-                       BF16 if wl.dtype == "bf16" else F32, wl.n_steps, iv, wl.lo, wl.hi)
+                       BF16 if wl.dtype == "bf16" else F32, wl.n_steps, iv, wl.lo, wl.hi, mask)
 
 
 def pab_workspace_bytes(cfg: pab_config) -> int:

@@ -246,6 +246,46 @@ def test_no_broadcast_baseline_computes_every_step(pab):
     assert ctx.pab_launch_count() == wl.n_steps
 
 
+def test_alternating_blocks_video(pab):
+    """A Latte-shaped small video (config 3's structure: even blocks spatial only, odd blocks temporal only, no cross
+    attention): with the per-block kind mask the slab holds one slot per block; every cell against the oracle's video
+    run, and the cells that a block does not have are refused."""
+    wl = W.Workload("alt_small", n_blocks=4, T=5, S=70, L=0, heads=3, head_dim=72, dtype="bf16", n_steps=8,
+                    intervals=(2, 3, 0), lo=1, hi=6, alternating=True, seed=0x50414299)
+    cfg = pab.config_of(wl)
+    slot = (wl.T * wl.S * wl.heads * wl.head_dim * 2 + 255) // 256 * 256
+    assert pab.pab_workspace_bytes(cfg) == 4 * slot
+    ctx = pab.PabContext(cfg, DEV)
+    ctx.workspace.fill_(0xFF)
+    assert [ctx.pab_slot_ptr(b, k) for b in range(4) for k in range(3)] == \
+        [ctx.workspace.data_ptr() + i * slot if k == i % 2 else 0 for i in range(4) for k in range(3)]
+    vo = orc.VideoOracle(wl.intervals, wl.lo, wl.hi)
+    last = {}
+    for step in range(wl.n_steps):
+        for block, kind in wl.calls_per_step():
+            want_dec = orc.schedule(step, wl.lo, wl.hi, wl.intervals[kind])
+            q = k = v = None
+            if want_dec == orc.COMPUTE:
+                q, k, v = W.make_qkv(wl, block, kind, step)
+            dec, ptr = ctx.pab_attention(block, kind, step, *(t.to(DEV) if t is not None else None for t in (q, k, v)))
+            torch.cuda.synchronize()
+            assert dec == want_dec and ptr == ctx.workspace.data_ptr() + block * slot
+            got = ctx.slot_tensor(block, kind)
+            _, want = vo.step(block, kind, step, lambda: W.make_qkv(wl, block, kind, step))
+            if dec == orc.COMPUTE:
+                assert_close(got, want, v, "alternating step %d block %d kind %d" % (step, block, kind))
+                last[block] = (got.clone(), v.abs().max().reshape(1))
+            else:
+                assert torch.equal(got.view(torch.int16), last[block][0].view(torch.int16))
+                assert_close(got, want, last[block][1], "alternating reuse")
+    assert ctx.pab_launch_count() == vo.computes
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl, 0, W.TEMPORAL, 0))
+    with pytest.raises(pab.PabError) as e:       # block 0 is a spatial block
+        ctx.pab_attention(0, W.TEMPORAL, 0, q, k, v)
+    assert e.value.status == pab.EINVAL
+    ctx.pab_destroy()
+
+
 FULL = [(wl, kind) for wl in W.CONFIGS[1:] for kind in (W.SPATIAL, W.TEMPORAL, W.CROSS) if wl.intervals[kind] > 0]
 
 

@@ -194,7 +194,12 @@ def test_workspace_bytes():
     slot = 16 * 1590 * 16 * 72 * 2
     assert slot % 256 == 0
     assert pab.pab_workspace_bytes(cfg) == 28 * 3 * slot
-    assert pab.pab_workspace_bytes(pab.config_of(W.LATTE_512)) == 28 * 2 * 16 * 1024 * 16 * 72 * 2
+    # alternating blocks (one kind each) get one slot per block; without the mask every block gets both kinds
+    assert pab.pab_workspace_bytes(pab.config_of(W.LATTE_512)) == 28 * 16 * 1024 * 16 * 72 * 2
+    wl = W.LATTE_512
+    unmasked = pab.make_config(wl.n_blocks, wl.T, wl.S, wl.L, wl.heads, wl.head_dim, pab.BF16, wl.n_steps, wl.intervals,
+                               wl.lo, wl.hi)
+    assert pab.pab_workspace_bytes(unmasked) == 28 * 2 * 16 * 1024 * 16 * 72 * 2
     tiny = pab.config_of(W.TINY)
     assert pab.pab_workspace_bytes(tiny) == 2 * 3 * 4 * 64 * 4 * 32 * 4
     bad = pab.config_of(W.TINY)
@@ -255,13 +260,34 @@ def test_create_and_attention_errors_without_device():
     assert pab.lib.pab_destroy(None) == pab.EINVAL and pab.lib.pab_reset(None) == pab.EINVAL
     assert pab.lib.pab_launch_count(None) == -1
 
-    # a config without cross attention has no cross slot and rejects cross calls
+    # a config without cross attention has no cross slot and rejects cross calls; its blocks alternate between
+    # spatial and temporal attention (block_kinds), so block b owns slot b and nothing else
     latte = pab.config_of(W.LATTE_512)
+    slot = 16 * 1024 * 16 * 72 * 2
     rc, h = _create(latte, fake, pab.pab_workspace_bytes(latte))
     assert rc == pab.OK
     assert pab.lib.pab_attention(h, 0, 2, 0, 16, 16, 16, None, ctypes.byref(out)) == pab.EINVAL
     assert pab.lib.pab_slot_ptr(h, 0, 2) is None
-    assert pab.lib.pab_slot_ptr(h, 1, 1) == fake + 3 * 16 * 1024 * 16 * 72 * 2
+    assert pab.lib.pab_slot_ptr(h, 0, 0) == fake and pab.lib.pab_slot_ptr(h, 0, 1) is None
+    assert pab.lib.pab_slot_ptr(h, 1, 1) == fake + slot and pab.lib.pab_slot_ptr(h, 1, 0) is None
+    assert pab.lib.pab_slot_ptr(h, 27, 1) == fake + 27 * slot
+    assert pab.lib.pab_attention(h, 1, 0, 0, 16, 16, 16, None, ctypes.byref(out)) == pab.EINVAL   # block 1 is temporal
+    assert "block_kinds" in pab.pab_last_error()
+    pab.lib.pab_destroy(h)
+    # the mask may only name kinds that have a broadcast range, and only the three kinds
+    wl = W.LATTE_512
+    for mask in ([4] + [1] * 27, [8] + [1] * 27):
+        bad = pab.make_config(wl.n_blocks, wl.T, wl.S, wl.L, wl.heads, wl.head_dim, pab.BF16, wl.n_steps, wl.intervals,
+                              wl.lo, wl.hi, mask)
+        assert _create(bad, fake, 1 << 40)[0] == pab.EINVAL and "block_kinds" in pab.pab_last_error()
+    # a mixed mask: block 0 has both kinds, block 1 none, block 2 temporal only
+    mixed = pab.make_config(3, wl.T, wl.S, wl.L, wl.heads, wl.head_dim, pab.BF16, wl.n_steps, wl.intervals, wl.lo, wl.hi,
+                            [3, 0, 2])
+    assert pab.pab_workspace_bytes(mixed) == 3 * slot
+    rc, h = _create(mixed, fake, 3 * slot)
+    assert rc == pab.OK
+    assert [pab.lib.pab_slot_ptr(h, b, k) for b in range(3) for k in range(2)] == \
+        [fake, fake + slot, None, None, None, fake + 2 * slot]
     pab.lib.pab_destroy(h)
 
 
