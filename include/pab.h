@@ -249,6 +249,26 @@ int pab_module_compute(int kind, int T, int S, int L, int heads, int head_dim, c
                        void *hip_stream);
 
 /*
+ * pab_module_compute for callers that cannot allocate device memory (code
+ * under HIP graph capture, serving loops and harnesses that forbid it): the
+ * same module with the same kernels, its scratch taken from an array inside
+ * the library (pab_module_static_scratch_bytes() = 16 MiB per GPU that the
+ * library runs on, held until the process ends) instead of from the caller.
+ * Allocates nothing and frees nothing; x, text, weights and out are still the
+ * caller's.  Shapes whose four scratch planes (each max(T*S, L) * heads *
+ * head_dim bf16 elements, rounded up to 256 bytes) exceed the array are
+ * refused with PAB_ENOMEM: use pab_module_compute for those.  All calls on one
+ * GPU share that GPU's array, whose planes are written in full before they
+ * are read within a call: calls that follow each other on one stream need no
+ * clearing in between, calls that overlap on one GPU (two streams, two
+ * threads) race.  Other errors as pab_module_compute, plus PAB_EDEVICE if the
+ * array's address cannot be obtained.
+ */
+size_t pab_module_static_scratch_bytes(void);
+int pab_module_compute_static(int kind, int T, int S, int L, int heads, int head_dim, const void *x,
+                              const void *text, const pab_module_weights *w, void *out, void *hip_stream);
+
+/*
  * pab_attention at module level (paper Sec. 2.3, Eq. 1 with the module output
  * as Y): on a computed step runs the module into cache slot (block, kind), on
  * a reused step launches nothing and reads nothing (x, text, w, scratch may be

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <mutex>
 #include <vector>
 
 #include "../../include/pab.h"
@@ -414,6 +415,32 @@ int launch_module(int kind, int T, int S, int L, int H, int D, const void *x, co
   return PAB_OK;
 }
 
+// ---- module scratch inside the library, for callers that cannot allocate.  One array per GPU the library is
+//      loaded on, held until the process ends; its device address is looked up once per device.  Every plane of
+//      it is written in full before it is read within a call, so nothing has to be cleared between calls. ----
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static __device__ __align__(256) __attribute__((used)) unsigned char g_static_scratch[STATIC_SCRATCH_BYTES];
+void *g_static_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES];   // device address per device ordinal, NULL until looked up
+std::mutex g_static_scratch_mutex;
+
+// device address of the scratch array on the current device (host code never uses the array's name for that)
+int static_scratch_of_current_device(void **ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(PAB_EDEVICE, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return fail(PAB_EDEVICE, "device ordinal %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+  if (!g_static_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess || !p) return fail(PAB_EDEVICE, "hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+    g_static_scratch_ptr[dev] = p;
+  }
+  *ptr = g_static_scratch_ptr[dev];
+  return PAB_OK;
+}
+
 // ---- the MLP module (paper Sec. 2.3, last sentence; App. A.2.2 MLP table) ----
 size_t mlp_scratch_bytes_of(long long n_tok, int C, int F) {
   const size_t h = ((size_t)n_tok * C * 2 + 255) / 256 * 256, u = ((size_t)n_tok * F * 2 + 255) / 256 * 256;
@@ -759,6 +786,24 @@ int pab_module_compute(int kind, int T, int S, int L, int heads, int head_dim, c
   if (rc != PAB_OK) return rc;
   if (!out || !aligned16(out)) return fail(PAB_EINVAL, "out must be non-NULL and 16-byte aligned");
   return launch_module(kind, T, S, L, heads, head_dim, x, text, w, scratch, scratch_bytes, out,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+size_t pab_module_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int pab_module_compute_static(int kind, int T, int S, int L, int heads, int head_dim, const void *x, const void *text,
+                              const pab_module_weights *w, void *out, void *hip_stream) {
+  const int rc = check_shape(kind, PAB_BF16, T, S, L, heads, head_dim);
+  if (rc != PAB_OK) return rc;
+  if (!out || !aligned16(out)) return fail(PAB_EINVAL, "out must be non-NULL and 16-byte aligned");
+  const size_t need = 4 * module_plane_bytes(T, S, L, heads, head_dim);
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(PAB_ENOMEM, "this shape needs %zu bytes of scratch, the built-in scratch holds %zu: use pab_module_compute",
+                need, STATIC_SCRATCH_BYTES);
+  void *scratch = nullptr;
+  const int rs = static_scratch_of_current_device(&scratch);
+  if (rs != PAB_OK) return rs;
+  return launch_module(kind, T, S, L, heads, head_dim, x, text, w, scratch, STATIC_SCRATCH_BYTES, out,
                        static_cast<hipStream_t>(hip_stream));
 }
 

@@ -24,6 +24,7 @@ BF16, F32 = 0, 1
 EXPORTS = (
     "pab_schedule", "pab_source_step", "pab_window_from_timesteps", "pab_preset", "pab_workspace_bytes", "pab_create", "pab_reset", "pab_attention",
     "pab_attention_compute", "pab_linear", "pab_module_scratch_bytes", "pab_module_compute", "pab_module_attention",
+    "pab_module_static_scratch_bytes", "pab_module_compute_static",
     "pab_mlp_schedule", "pab_mlp_source_step", "pab_steps_from_timesteps", "pab_mlp_scratch_bytes", "pab_mlp_compute",
     "pab_mlp_workspace_bytes", "pab_mlp_create", "pab_mlp_reset", "pab_mlp", "pab_mlp_launch_count", "pab_mlp_slot_ptr",
     "pab_mlp_destroy",
@@ -92,6 +93,10 @@ def _load() -> ctypes.CDLL:
     lib.pab_module_scratch_bytes.argtypes = [ctypes.POINTER(pab_config)]
     lib.pab_module_compute.restype = ci
     lib.pab_module_compute.argtypes = [ci] * 6 + [vp, vp, ctypes.POINTER(pab_module_weights), vp, ctypes.c_size_t, vp, vp]
+    lib.pab_module_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.pab_module_static_scratch_bytes.argtypes = []
+    lib.pab_module_compute_static.restype = ci
+    lib.pab_module_compute_static.argtypes = [ci] * 6 + [vp, vp, ctypes.POINTER(pab_module_weights), vp, vp]
     lib.pab_module_attention.restype = ci
     lib.pab_module_attention.argtypes = [vp, ci, ci, ci, vp, vp, ctypes.POINTER(pab_module_weights), vp,
                                          ctypes.c_size_t, vp, ctypes.POINTER(vp)]
@@ -373,6 +378,20 @@ def pab_module_compute(kind: int, x, text, w: pab_module_weights, heads: int, sc
         out = torch.empty_like(x)
     _check(lib.pab_module_compute(kind, T, S, L, heads, D, _ptr(x), _ptr(text) if text is not None else None,
                                   ctypes.byref(w), _ptr(scratch), scratch.numel(), _ptr(out), _stream(stream)))
+    return out
+
+
+def pab_module_static_scratch_bytes() -> int:
+    return lib.pab_module_static_scratch_bytes()
+
+
+def pab_module_compute_static(kind: int, x, text, w: pab_module_weights, heads: int, out, stream=None):
+    """pab_module_compute with the library's built-in scratch: nothing is allocated, ``out`` is the caller's."""
+    T, S, C = x.shape
+    D = C // heads
+    L = text.shape[0] if text is not None else 0
+    _check(lib.pab_module_compute_static(kind, T, S, L, heads, D, _ptr(x), _ptr(text) if text is not None else None,
+                                         ctypes.byref(w), _ptr(out), _stream(stream)))
     return out
 
 
