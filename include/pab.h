@@ -180,7 +180,7 @@ int pab_attention_compute(int kind, int dtype, int T, int S, int L, int heads, i
 
 /*
  * A projection of the attention module (paper App. B.5: "qkv proj", "o proj";
- * App. B.6: q,k,v = proj(x), o = proj(o)): C = A W^T + bias, one kernel launch
+ * the first and the last step of the workflow of App. B.6): C = A W^T + bias, one kernel launch
  * on `hip_stream`.  A: [M, K] activations, W: [N, K] weights (row n produces
  * feature n), bias: [N] or NULL, C: [M, N] written with a row pitch of `ldc`
  * elements (ldc >= N; ldc > N lets several projections write side by side).
