@@ -246,6 +246,51 @@ def test_no_broadcast_baseline_computes_every_step(pab):
     assert ctx.pab_launch_count() == wl.n_steps
 
 
+def test_tensors_beyond_four_gigabytes(pab):
+    """Maximum sizes: q, k, v, o of 2.2 G elements (4.4 GB each), so element offsets pass 2^31 and byte offsets
+    2^32 inside every tensor.  Spatial (2400 frames), temporal (120 000 positions per frame, 276 MB between the
+    frames of a problem) and cross attention over the same buffers; frames / positions / tokens at the start, on
+    both sides of the 2^31-element mark and at the very end are compared with the oracle, the rest is checked to
+    be written and finite.  Inputs: torch's seeded generator on the device (N(0,1) rounded to bf16)."""
+    H, D = 16, 72
+    n = 2400 * 800 * H * D
+    assert n > 2 ** 31
+    g = torch.Generator(device=DEV)
+    g.manual_seed(0x50414277)
+    flat = [torch.randn(n, generator=g, device=DEV, dtype=torch.bfloat16) for _ in range(3)]
+    out = torch.empty(n, device=DEV, dtype=torch.bfloat16)
+    text_k, text_v = (torch.randn((120, H, D), generator=g, device=DEV, dtype=torch.bfloat16) for _ in range(2))
+
+    def check(kind, T, S, picks):
+        print("big", W.KIND_NAMES[kind], T, S, flush=True)
+        q, k, v = (t.view(T, S, H, D) for t in flat)
+        o = out.view(T, S, H, D)
+        out.view(torch.int16).fill_(-1)                 # bf16 NaN pattern
+        if kind == W.CROSS:
+            pab.pab_attention_compute(kind, q, text_k, text_v, out=o)
+        else:
+            pab.pab_attention_compute(kind, q, k, v, out=o)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all()), "unwritten or non-finite output"
+        for pick in picks:
+            if kind == W.SPATIAL:      # one frame is one batch entry
+                sl = (slice(pick, pick + 1),)
+            elif kind == W.TEMPORAL:   # one position is one batch entry
+                sl = (slice(None), slice(pick, pick + 1))
+            else:                      # eight tokens of frame pick
+                sl = (slice(pick, pick + 1), slice(S - 8, S))
+            qs, ks, vs = (t[sl].cpu() for t in (q, k, v))
+            if kind == W.CROSS:
+                ks, vs = text_k.cpu(), text_v.cpu()
+            want = orc.kind_attention(kind, qs, ks, vs)
+            assert_close(o[sl], want, vs, "big %s at %d" % (W.KIND_NAMES[kind], pick))
+
+    mark = 2 ** 31 // (800 * H * D)                     # frame that holds element 2^31
+    check(W.SPATIAL, 2400, 800, [0, mark - 1, mark, mark + 1, 2399])
+    check(W.CROSS, 2400, 800, [0, mark, 2399])
+    check(W.TEMPORAL, 16, 120000, [0, 59999, 119999])   # every problem spans 15 x 276 MB
+
+
 def test_alternating_blocks_video(pab):
     """A Latte-shaped small video (config 3's structure: even blocks spatial only, odd blocks temporal only, no cross
     attention): with the per-block kind mask the slab holds one slot per block; every cell against the oracle's video
