@@ -7,12 +7,12 @@ without the library; everything else comes from ``paper_2408_12588_amd.pab``,
 which loads ``libpab.so`` and raises if it has not been built.
 """
 import importlib
-
-_PAB_NAMES = None
+import importlib.util
 
 
 def __getattr__(name):
-    if name in ("pab", "workloads"):
+    # submodules (pab, workloads, build) import as themselves: build must be reachable before the library exists
+    if not name.startswith("_") and importlib.util.find_spec(__name__ + "." + name) is not None:
         return importlib.import_module("." + name, __name__)
     pab = importlib.import_module(".pab", __name__)
     if hasattr(pab, name):
