@@ -255,6 +255,8 @@ def main():
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
+    from paper_2408_12588_amd import build as pab_build
+    pab_build.ensure_built()                   # loads what is built; builds only if nothing is
     from paper_2408_12588_amd import pab, workloads as W
 
     wl = W.BY_NAME[args.workload]

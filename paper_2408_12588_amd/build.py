@@ -40,6 +40,11 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build the library only if none is there: callers load what is built."""
+    return LIB if os.path.exists(LIB) else build_lib()
+
+
 def device_asm(path: str, extra_flags=()) -> str:
     """Write the gfx950 assembly of the device code (same flags as the library) to `path`."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

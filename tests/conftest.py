@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; only a tree in which nothing is built yet gets built here
+    from paper_2408_12588_amd import build as pab_build
+    pab_build.ensure_built()
 
 
 def golden_path(name):
