@@ -382,6 +382,7 @@ def main():
         h = Harness(wl, dev, args.pool)
     if not args.no_mfma_reference and wl.dtype == "bf16":
         result["mfma_reference"] = mfma_reference(dev)
+        result["hbm_reference"] = hbm_reference(dev, wl)
     if not args.no_module and wl.dtype == "bf16":
         result["module"] = module_section(wl, h.pool, args, dev)
     if not args.no_cpu_baseline:
@@ -414,6 +415,44 @@ def mfma_reference(dev, n=8192, reps=20):
         tf = 2.0 * n ** 3 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
         res[name] = round(tf, 1)
         res[name + "_frac_of_peak"] = round(tf / PEAK_BF16_TFLOPS, 4)
+    return res
+
+
+def hbm_reference(dev, wl, n=1 << 29, reps=10):
+    """Context for the HBM roofline fractions, not part of the path: what contiguous streams sustain on this machine, with
+    torch's own elementwise kernels: a device copy (one read, one write) and q + k * v (three reads, one write: the
+    traffic mix of an attention call), on 1 GiB bf16 tensors and, for the second, on tensors of the workload's own
+    size (eight rotating sets, so that nothing is found in the last-level cache; launches this short carry their
+    ramp-up and drain like the attention kernels do)."""
+    import torch
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    stream = torch.cuda.current_stream()
+
+    def rate(fn, nbytes, calls):
+        for i in range(2):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(calls):
+            fn(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return nbytes * calls / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    q, k, v = (torch.randn(n, generator=gen, device=dev, dtype=torch.bfloat16) for _ in range(3))
+    o = torch.empty_like(q)
+    res = {"what": "torch copy_ and addcmul on %d MiB bf16 tensors (%d back-to-back calls) and on [T,S,H,D] tensors of "
+                   "the workload (8 rotating sets, 40 calls)" % (n * 2 >> 20, reps), "unit": "GB/s"}
+    res["copy"] = round(rate(lambda i: o.copy_(q), 2 * n * 2, reps), 1)
+    res["three_reads_one_write"] = round(rate(lambda i: torch.addcmul(q, k, v, out=o), 4 * n * 2, reps), 1)
+    del q, k, v, o
+    m = wl.T * wl.S * wl.heads * wl.head_dim
+    sets = [[torch.randn(m, generator=gen, device=dev, dtype=torch.bfloat16) for _ in range(4)] for _ in range(8)]
+    res["three_reads_one_write_workload_size"] = round(
+        rate(lambda i: torch.addcmul(sets[i % 8][0], sets[i % 8][1], sets[i % 8][2], out=sets[(i + 3) % 8][3]), 4 * m * 2, 40), 1)
+    for key in ("copy", "three_reads_one_write", "three_reads_one_write_workload_size"):
+        res[key + "_frac_of_peak"] = round(res[key] / PEAK_HBM_GBS, 4)
     return res
 
 
