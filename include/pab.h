@@ -12,7 +12,9 @@
  * Conventions
  *   - All tensor pointers are DEVICE pointers owned by the caller, 16-byte
  *     aligned, dense, in the layouts given below.  The library never allocates,
- *     frees or copies device memory and never synchronises a stream.
+ *     frees or copies device memory and never synchronises a stream (the one
+ *     piece of device memory of its own is the fixed array behind
+ *     pab_module_compute_static, part of its code object).
  *   - Activations are laid out [T, S, H, D]: T latent frames, S tokens per
  *     frame, H heads, D head dim, D contiguous.  Spatial and temporal attention
  *     read the same buffers (batch = T / sequence = S, resp. batch = S /
